@@ -1,0 +1,185 @@
+/*
+ * moespec.h - C ABI of the budgeted MoE-layer forward that verifies an M-token draft tree
+ * (MoE-Spec expert budgeting), implemented as HIP kernels for gfx950 (MI355X).
+ *
+ * The calls follow the paper's problem statement (Algorithm 1: "hidden states h_1..h_M, budget B,
+ * policy -> MoE output for each token") split at its three stages:
+ *
+ *   moespec_route          Eq. (1) router softmax, Section 2.1 per-token top-k and mixing weights
+ *   moespec_budget         Eq. (5) per-expert aggregation, top-B shortlist (Section 3.2), Eq. (7)/(8)
+ *                          restriction of every token's routing (Section 3.3), grouping into per-expert
+ *                          segments
+ *   moespec_expert_ffn     the expert networks of Eq. (2)/(7)/(8) run over the loaded experts only,
+ *                          and the weighted combine
+ *   moespec_layer_forward  all of the above in one call (Algorithm 1)
+ *
+ * Conventions (all calls)
+ *   Pointers  Every buffer pointer is a DEVICE pointer unless it is a descriptor struct
+ *             (moespec_desc, moespec_weights are read on the host).  All tensors are row-major,
+ *             contiguous and 16-byte aligned.  "dtype" tensors hold float (MOESPEC_F32) or bfloat16
+ *             bit patterns (MOESPEC_BF16).
+ *   Ownership The caller owns every buffer, workspace included.  The library allocates nothing,
+ *             frees nothing and keeps no pointer after a call returns; it holds no global state.
+ *   Execution A call validates its arguments on the host, enqueues kernels on `hip_stream`
+ *             (a hipStream_t passed as void*; NULL = the default stream) and returns without
+ *             synchronising.  Nothing is copied to the host; data-dependent quantities (the number
+ *             of loaded experts, segment sizes) stay on the device.
+ *   Workspace `ws` must hold at least moespec_workspace_bytes(desc, M) bytes, 256-byte aligned.
+ *             Its contents are scratch: undefined before and after a call.  Calls that share a
+ *             workspace must be ordered on one stream.
+ *   Errors    Every call returns a moespec_status.  Argument errors are detected before any launch
+ *             and leave all buffers untouched.  HIP launch failures are reported as
+ *             MOESPEC_ERR_HIP.  Nothing throws or aborts across this boundary.
+ *   Decisions Routing probabilities, aggregate scores and every ranking are computed in fp64;
+ *             every tie goes to the lowest expert id.  Rankings compare routing probabilities.
+ *   Determinism  Same inputs give bit-identical outputs on every call (no floating-point atomics).
+ */
+#ifndef MOESPEC_H
+#define MOESPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOESPEC_OK = 0,
+  MOESPEC_ERR_INVALID_ARG = 1,       /* null pointer, size out of range, B < k under substitution, ... */
+  MOESPEC_ERR_UNSUPPORTED_SHAPE = 2, /* a shape the kernels do not cover (see moespec_check_desc)     */
+  MOESPEC_ERR_WORKSPACE_TOO_SMALL = 3,
+  MOESPEC_ERR_HIP = 4                /* a HIP runtime call failed (no device, launch error)           */
+} moespec_status;
+
+typedef enum { MOESPEC_F32 = 0, MOESPEC_BF16 = 1 } moespec_dtype;
+
+/* Coverage policy of Section 3.3: Eq. (7) truncation or Eq. (8) substitution. */
+typedef enum { MOESPEC_TRUNCATE = 0, MOESPEC_SUBSTITUTE = 1 } moespec_policy;
+
+/* Shape of one MoE layer.  Host struct. */
+typedef struct {
+  int32_t d;         /* hidden size                                                         */
+  int32_t n_experts; /* N                                                                   */
+  int32_t top_k;     /* k, 1 <= k <= N                                                      */
+  int32_t d_ff;      /* expert intermediate size F                                          */
+  int32_t dtype;     /* moespec_dtype: storage of h, the weights, residual and out          */
+  int32_t renorm;    /* 0: mixing weights are the raw g_i; 1: g_i / sum over the selected   */
+                     /* set (Section 2.1: "depending on the architecture")                  */
+} moespec_desc;
+
+/* Weights of one MoE layer.  Host struct holding device pointers. */
+typedef struct {
+  const void  *w_router; /* [N, d]    dtype, row i is the routing vector w_i of Eq. (1)      */
+  const float *b_router; /* [N] float or NULL; added to the router projection before softmax */
+  const void  *w_gate;   /* [N, F, d] dtype                                                  */
+  const void  *w_up;     /* [N, F, d] dtype                                                  */
+  const void  *w_down;   /* [N, d, F] dtype;  E_i(x) = w_down_i (silu(w_gate_i x) * w_up_i x) */
+} moespec_weights;
+
+/* Library ABI version (bumped on any signature change). */
+int32_t moespec_abi_version(void);
+
+/* Human-readable name of a status code; never NULL. */
+const char *moespec_status_string(int32_t status);
+
+/*
+ * Checks that the kernels cover this layer shape: d and d_ff multiples of 32 (bf16) or 4 (f32),
+ * 1 <= top_k <= n_experts <= 1024, top_k <= 64, dtype and renorm valid.
+ * Returns MOESPEC_OK, MOESPEC_ERR_INVALID_ARG or MOESPEC_ERR_UNSUPPORTED_SHAPE.  Host only.
+ */
+moespec_status moespec_check_desc(const moespec_desc *desc);
+
+/*
+ * Bytes of workspace any call below needs for trees of up to M_max tokens (0 on an invalid
+ * descriptor or M_max < 1).  Host only.
+ */
+size_t moespec_workspace_bytes(const moespec_desc *desc, int32_t M_max);
+
+/*
+ * Stage 1 of Algorithm 1 - Eq. (1) and Section 2.1.
+ *   h        [M, d] dtype   in   draft-tree hidden rows
+ *   probs    [M, N] double  out  g_i(h_t), softmax over all N experts of w_i . h_t (+ b_i)
+ *   topk_ids [M, k] int32   out  T_k(h_t), best first (ties: lowest id)
+ *   topk_w   [M, k] float   out  mixing weights of those slots (raw or renormalised over T_k)
+ * topk_ids and topk_w may both be NULL.  1 <= M <= 65535.
+ */
+moespec_status moespec_route(const moespec_desc *desc, const moespec_weights *weights,
+                             const void *h, int32_t M,
+                             double *probs, int32_t *topk_ids, float *topk_w,
+                             void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Stages 2-3 of Algorithm 1 without the expert maths - Eq. (5), Section 3.2, Eq. (7)/(8).
+ *   probs         [M, N] double in   routing probabilities (as written by moespec_route)
+ *   B                           in   expert budget, 1 <= B <= N; substitution needs B >= k
+ *   ext_shortlist [B] int32     in   NULL = router-based ranking (Eq. (5)); otherwise B distinct
+ *                                    expert ids fixed elsewhere (e.g. the static ranking of Eq. (4)),
+ *                                    used as the shortlist S verbatim
+ *   scores        [N] double    out  s_i = sum_t g_i(h_t)                      (may be NULL)
+ *   budget_ids    [B] int32     out  S in rank order (best first)              (may be NULL)
+ *   tok_ids       [M, k] int32  out  restricted routing; -1 marks a dropped slot.  Truncation keeps the
+ *                                    natural slot order; substitution lists the top-k inside S best first
+ *   tok_w         [M, k] float  out  mixing weights; truncation keeps the weights of the natural top-k
+ *                                    unchanged, dropped slots get 0
+ *   seg_expert    [B] int32     out  S in ascending expert id
+ *   seg_off       [B+1] int32   out  offsets of each expert's segment in perm (empty segments allowed)
+ *   perm          [M*k] int32   out  surviving (token, slot) pairs as flat indices t*k+slot, ordered by
+ *                                    (expert id, token); entries past seg_off[B] are -1
+ *   n_loaded      [1] int32     out  number of non-empty segments = experts loaded (may be NULL)
+ */
+moespec_status moespec_budget(const moespec_desc *desc, const double *probs, int32_t M, int32_t B,
+                              int32_t policy, const int32_t *ext_shortlist,
+                              double *scores, int32_t *budget_ids,
+                              int32_t *tok_ids, float *tok_w,
+                              int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
+                              void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * The expert networks over the loaded experts and the weighted combine - Eq. (2)/(7)/(8).
+ * For every segment i with at least one pair, expert seg_expert[i] is applied to the hidden rows of
+ * its pairs, streaming that expert's three matrices from memory once; then
+ *   out[t] = (residual ? residual[t] : 0) + sum over surviving slots, in slot order, tok_w[t,slot] * E(h_t).
+ * A token with no surviving slot gets exactly residual[t] (or 0).
+ *   n_seg                       in   number of segments (the B of moespec_budget), 1 <= n_seg <= N
+ *   seg_expert, seg_off, perm, tok_ids, tok_w   in   as written by moespec_budget
+ *   residual [M, d] dtype       in   NULL or the residual stream to add
+ *   out      [M, d] dtype       out
+ */
+moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weights *weights,
+                                  const void *h, int32_t M, int32_t n_seg,
+                                  const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
+                                  const int32_t *tok_ids, const float *tok_w,
+                                  const void *residual, void *out,
+                                  void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Algorithm 1 end to end: route, aggregate, shortlist, restrict, experts, combine.
+ * B = N is the unbudgeted layer of Eq. (2), which loads the expert union of Eq. (3).
+ * The tap pointers (all optional, any may be NULL) receive copies of the intermediates with the
+ * shapes documented above: probs [M,N], scores [N], budget_ids [B], tok_ids [M,k], tok_w [M,k],
+ * seg_expert [B], seg_off [B+1], perm [M*k], n_loaded [1].
+ */
+typedef struct {
+  double  *probs;
+  double  *scores;
+  int32_t *budget_ids;
+  int32_t *tok_ids;
+  float   *tok_w;
+  int32_t *seg_expert;
+  int32_t *seg_off;
+  int32_t *perm;
+  int32_t *n_loaded;
+} moespec_taps;
+
+moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_weights *weights,
+                                     const void *h, int32_t M, int32_t B, int32_t policy,
+                                     const int32_t *ext_shortlist,
+                                     const void *residual, void *out,
+                                     const moespec_taps *taps,
+                                     void *ws, size_t ws_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOESPEC_H */

@@ -52,9 +52,13 @@ def _f64(x) -> np.ndarray:
 # --------------------------------------------------------------------------- Eq. (1)
 def router_logits(h, w_router, b_router=None) -> np.ndarray:
     """logit[t, i] = w_i . h_t (+ b_i).  h[M, d], w_router[N, d] -> [M, N] fp64."""
-    logits = _f64(h) @ _f64(w_router).T
-    if b_router is not None:
-        logits = logits + _f64(b_router)[None, :]
+    h, w_router = _f64(h), _f64(w_router)
+    logits = np.empty((h.shape[0], w_router.shape[0]), dtype=np.float64)
+    for t in range(h.shape[0]):
+        for i in range(w_router.shape[0]):
+            logits[t, i] = np.dot(w_router[i], h[t])      # one routine for every (t, i): equal rows give equal logits
+            if b_router is not None:
+                logits[t, i] += float(b_router[i])
     return logits
 
 

@@ -1,0 +1,253 @@
+"""ctypes binding of libmoespec.so: argument marshalling only.
+
+Every function takes torch tensors living on the GPU (device memory and streams are PyTorch's
+job here), checks dtype / shape / contiguity, passes raw pointers and sizes through the C ABI and
+raises ``MoeSpecError`` on a non-zero status.  No step of the method is computed in Python.
+The library must have been built (``python -m paper_2602_16052_amd.build``); there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_int32, c_size_t, c_void_p
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libmoespec.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = range(5)
+F32, BF16 = 0, 1
+TRUNCATE, SUBSTITUTE = 0, 1
+
+EXPORTS = ("moespec_abi_version", "moespec_status_string", "moespec_check_desc", "moespec_workspace_bytes",
+           "moespec_route", "moespec_budget", "moespec_expert_ffn", "moespec_layer_forward")
+
+
+class MoeSpecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class Desc(Structure):
+    _fields_ = [("d", c_int32), ("n_experts", c_int32), ("top_k", c_int32), ("d_ff", c_int32),
+                ("dtype", c_int32), ("renorm", c_int32)]
+
+
+class Weights(Structure):
+    _fields_ = [("w_router", c_void_p), ("b_router", c_void_p), ("w_gate", c_void_p), ("w_up", c_void_p),
+                ("w_down", c_void_p)]
+
+
+class Taps(Structure):
+    _fields_ = [("probs", c_void_p), ("scores", c_void_p), ("budget_ids", c_void_p), ("tok_ids", c_void_p),
+                ("tok_w", c_void_p), ("seg_expert", c_void_p), ("seg_off", c_void_p), ("perm", c_void_p),
+                ("n_loaded", c_void_p)]
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """dlopen the library and declare its signatures.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise FileNotFoundError(f"{p} is missing: build it with `python -m paper_2602_16052_amd.build` "
+                                "(there is no non-HIP fallback)")
+    lib = ctypes.CDLL(p)
+    lib.moespec_abi_version.restype = c_int32
+    lib.moespec_abi_version.argtypes = []
+    lib.moespec_status_string.restype = c_char_p
+    lib.moespec_status_string.argtypes = [c_int32]
+    lib.moespec_check_desc.restype = c_int32
+    lib.moespec_check_desc.argtypes = [POINTER(Desc)]
+    lib.moespec_workspace_bytes.restype = c_size_t
+    lib.moespec_workspace_bytes.argtypes = [POINTER(Desc), c_int32]
+    lib.moespec_route.restype = c_int32
+    lib.moespec_route.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_void_p, c_void_p, c_void_p,
+                                  c_void_p, c_size_t, c_void_p]
+    lib.moespec_budget.restype = c_int32
+    lib.moespec_budget.argtypes = [POINTER(Desc), c_void_p, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
+                                   c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                   c_void_p]
+    lib.moespec_expert_ffn.restype = c_int32
+    lib.moespec_expert_ffn.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_void_p,
+                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                       c_size_t, c_void_p]
+    lib.moespec_layer_forward.restype = c_int32
+    lib.moespec_layer_forward.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_int32,
+                                          c_void_p, c_void_p, c_void_p, POINTER(Taps), c_void_p, c_size_t, c_void_p]
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().moespec_status_string(int(status)).decode()
+
+
+def abi_version() -> int:
+    return int(load_library().moespec_abi_version())
+
+
+@dataclass
+class LayerDesc:
+    d: int
+    n_experts: int
+    top_k: int
+    d_ff: int
+    dtype: int          # F32 or BF16
+    renorm: bool
+
+    def c(self) -> Desc:
+        return Desc(self.d, self.n_experts, self.top_k, self.d_ff, self.dtype, int(self.renorm))
+
+    @property
+    def torch_dtype(self) -> torch.dtype:
+        return torch.bfloat16 if self.dtype == BF16 else torch.float32
+
+
+def check_desc(desc: LayerDesc) -> int:
+    c = desc.c()
+    return int(load_library().moespec_check_desc(ctypes.byref(c)))
+
+
+def workspace_bytes(desc: LayerDesc, M_max: int) -> int:
+    c = desc.c()
+    return int(load_library().moespec_workspace_bytes(ctypes.byref(c), int(M_max)))
+
+
+def alloc_workspace(desc: LayerDesc, M_max: int, device="cuda") -> torch.Tensor:
+    n = workspace_bytes(desc, M_max)
+    if n == 0:
+        raise MoeSpecError(ERR_INVALID_ARG, "moespec_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype] = None, numel: Optional[int] = None,
+         name: str = "tensor") -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name} needs at least {numel} elements, got {t.numel()}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _weights(desc: LayerDesc, w: Dict[str, torch.Tensor], router: bool, experts: bool) -> Weights:
+    N, d, F, dt = desc.n_experts, desc.d, desc.d_ff, desc.torch_dtype
+    cw = Weights()
+    if router:
+        cw.w_router = _ptr(w["w_router"], dt, N * d, "w_router")
+        cw.b_router = _ptr(w.get("b_router"), torch.float32, N, "b_router")
+    if experts:
+        cw.w_gate = _ptr(w["w_gate"], dt, N * F * d, "w_gate")
+        cw.w_up = _ptr(w["w_up"], dt, N * F * d, "w_up")
+        cw.w_down = _ptr(w["w_down"], dt, N * d * F, "w_down")
+    return cw
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise MoeSpecError(int(status), where)
+
+
+def moespec_route(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: torch.Tensor, ws: torch.Tensor,
+                  stream=None, want_topk: bool = True):
+    """Eq. (1) + Section 2.1.  Returns dict(probs[M,N] f64, topk_ids[M,k] i32, topk_w[M,k] f32)."""
+    M, N, k = h.shape[0], desc.n_experts, desc.top_k
+    dev = h.device
+    probs = torch.empty((M, N), dtype=torch.float64, device=dev)
+    ids = torch.empty((M, k), dtype=torch.int32, device=dev) if want_topk else None
+    tw = torch.empty((M, k), dtype=torch.float32, device=dev) if want_topk else None
+    cd, cw = desc.c(), _weights(desc, weights, True, False)
+    st = load_library().moespec_route(ctypes.byref(cd), ctypes.byref(cw), _ptr(h, desc.torch_dtype, M * desc.d, "h"),
+                                      M, _ptr(probs), _ptr(ids), _ptr(tw), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "moespec_route")
+    return dict(probs=probs, topk_ids=ids, topk_w=tw)
+
+
+def moespec_budget(desc: LayerDesc, probs: torch.Tensor, B: int, policy: int, ws: torch.Tensor,
+                   ext_shortlist: Optional[torch.Tensor] = None, stream=None):
+    """Eq. (5), shortlist, Eq. (7)/(8), segments.  Returns a dict of the documented outputs."""
+    M, N, k = probs.shape[0], desc.n_experts, desc.top_k
+    dev = probs.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    out = dict(scores=torch.empty(N, dtype=torch.float64, device=dev), budget_ids=torch.empty(max(B, 1), **i32),
+               tok_ids=torch.empty((M, k), **i32), tok_w=torch.empty((M, k), dtype=torch.float32, device=dev),
+               seg_expert=torch.empty(max(B, 1), **i32), seg_off=torch.empty(max(B, 1) + 1, **i32),
+               perm=torch.empty(M * k, **i32), n_loaded=torch.empty(1, **i32))
+    cd = desc.c()
+    st = load_library().moespec_budget(
+        ctypes.byref(cd), _ptr(probs, torch.float64, M * N, "probs"), M, int(B), int(policy),
+        _ptr(ext_shortlist, torch.int32, max(B, 0), "ext_shortlist"), _ptr(out["scores"]), _ptr(out["budget_ids"]),
+        _ptr(out["tok_ids"]), _ptr(out["tok_w"]), _ptr(out["seg_expert"]), _ptr(out["seg_off"]), _ptr(out["perm"]),
+        _ptr(out["n_loaded"]), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "moespec_budget")
+    return out
+
+
+def moespec_expert_ffn(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: torch.Tensor, seg_expert: torch.Tensor,
+                       seg_off: torch.Tensor, perm: torch.Tensor, tok_ids: torch.Tensor, tok_w: torch.Tensor,
+                       ws: torch.Tensor, residual: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                       stream=None) -> torch.Tensor:
+    """Experts over the loaded set + weighted combine.  Returns out[M, d] in the layer dtype."""
+    M, k, dt = h.shape[0], desc.top_k, desc.torch_dtype
+    n_seg = seg_expert.numel()
+    if out is None:
+        out = torch.empty((M, desc.d), dtype=dt, device=h.device)
+    cd, cw = desc.c(), _weights(desc, weights, False, True)
+    st = load_library().moespec_expert_ffn(
+        ctypes.byref(cd), ctypes.byref(cw), _ptr(h, dt, M * desc.d, "h"), M, n_seg,
+        _ptr(seg_expert, torch.int32, n_seg, "seg_expert"), _ptr(seg_off, torch.int32, n_seg + 1, "seg_off"),
+        _ptr(perm, torch.int32, M * k, "perm"), _ptr(tok_ids, torch.int32, M * k, "tok_ids"),
+        _ptr(tok_w, torch.float32, M * k, "tok_w"), _ptr(residual, dt, M * desc.d, "residual"),
+        _ptr(out, dt, M * desc.d, "out"), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "moespec_expert_ffn")
+    return out
+
+
+def moespec_layer_forward(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: torch.Tensor, B: int, policy: int,
+                          ws: torch.Tensor, ext_shortlist: Optional[torch.Tensor] = None,
+                          residual: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                          taps: bool = False, stream=None):
+    """Algorithm 1 in one call.  Returns ``out`` or, with ``taps=True``, ``(out, dict of intermediates)``."""
+    M, N, k, dt = h.shape[0], desc.n_experts, desc.top_k, desc.torch_dtype
+    dev = h.device
+    if out is None:
+        out = torch.empty((M, desc.d), dtype=dt, device=dev)
+    tap_t = None
+    ctaps = None
+    if taps:
+        i32 = dict(dtype=torch.int32, device=dev)
+        nb = max(int(B), 1)
+        tap_t = dict(probs=torch.empty((M, N), dtype=torch.float64, device=dev),
+                     scores=torch.empty(N, dtype=torch.float64, device=dev), budget_ids=torch.empty(nb, **i32),
+                     tok_ids=torch.empty((M, k), **i32), tok_w=torch.empty((M, k), dtype=torch.float32, device=dev),
+                     seg_expert=torch.empty(nb, **i32), seg_off=torch.empty(nb + 1, **i32),
+                     perm=torch.empty(M * k, **i32), n_loaded=torch.empty(1, **i32))
+        ctaps = Taps(**{key: _ptr(val) for key, val in tap_t.items()})
+    cd, cw = desc.c(), _weights(desc, weights, True, True)
+    st = load_library().moespec_layer_forward(
+        ctypes.byref(cd), ctypes.byref(cw), _ptr(h, dt, M * desc.d, "h"), M, int(B), int(policy),
+        _ptr(ext_shortlist, torch.int32, max(int(B), 0), "ext_shortlist"), _ptr(residual, dt, M * desc.d, "residual"),
+        _ptr(out, dt, M * desc.d, "out"), ctypes.byref(ctaps) if ctaps is not None else None, _ptr(ws), ws.numel(),
+        _stream(stream))
+    _check(st, "moespec_layer_forward")
+    return (out, tap_t) if taps else out

@@ -1,0 +1,148 @@
+// C ABI of the library: argument validation (host only, before any launch), workspace carve-up,
+// and the sequencing of the kernel launchers.
+#include "common.h"
+
+using namespace moespec;
+
+namespace {
+
+constexpr int kMaxExperts = 1024;
+constexpr int kMaxTopK = 64;
+constexpr int kMaxHidden = 8192;
+constexpr int kMaxTokens = 65535;
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+moespec_status check_desc(const moespec_desc *ds) {
+  if (!ds) return MOESPEC_ERR_INVALID_ARG;
+  if (ds->dtype != MOESPEC_F32 && ds->dtype != MOESPEC_BF16) return MOESPEC_ERR_INVALID_ARG;
+  if (ds->renorm != 0 && ds->renorm != 1) return MOESPEC_ERR_INVALID_ARG;
+  if (ds->d < 1 || ds->d_ff < 1 || ds->n_experts < 1) return MOESPEC_ERR_INVALID_ARG;
+  if (ds->top_k < 1 || ds->top_k > ds->n_experts) return MOESPEC_ERR_INVALID_ARG;
+  if (ds->n_experts > kMaxExperts || ds->top_k > kMaxTopK || ds->d > kMaxHidden)
+    return MOESPEC_ERR_UNSUPPORTED_SHAPE;
+  const int mult = ds->dtype == MOESPEC_BF16 ? 32 : 4;
+  if (ds->d % mult != 0 || ds->d_ff % mult != 0) return MOESPEC_ERR_UNSUPPORTED_SHAPE;
+  if ((int64_t)ds->n_experts * ds->d_ff * ds->d >= (int64_t)1 << 40) return MOESPEC_ERR_UNSUPPORTED_SHAPE;
+  return MOESPEC_OK;
+}
+
+moespec_status check_common(const moespec_desc *ds, int32_t M, const void *ws, size_t ws_bytes) {
+  moespec_status s = check_desc(ds);
+  if (s != MOESPEC_OK) return s;
+  if (M < 1 || M > kMaxTokens) return MOESPEC_ERR_INVALID_ARG;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOESPEC_ERR_INVALID_ARG;
+  if (ws_bytes < carve_workspace(*ds, M, nullptr).bytes) return MOESPEC_ERR_WORKSPACE_TOO_SMALL;
+  return MOESPEC_OK;
+}
+
+moespec_status check_weights(const moespec_weights *wt, bool router, bool experts) {
+  if (!wt) return MOESPEC_ERR_INVALID_ARG;
+  if (router && (!wt->w_router || !aligned16(wt->w_router))) return MOESPEC_ERR_INVALID_ARG;
+  if (experts && (!wt->w_gate || !wt->w_up || !wt->w_down || !aligned16(wt->w_gate) || !aligned16(wt->w_up) ||
+                  !aligned16(wt->w_down)))
+    return MOESPEC_ERR_INVALID_ARG;
+  return MOESPEC_OK;
+}
+
+moespec_status check_budget(const moespec_desc *ds, int32_t B, int32_t policy) {
+  if (policy != MOESPEC_TRUNCATE && policy != MOESPEC_SUBSTITUTE) return MOESPEC_ERR_INVALID_ARG;
+  if (B < 1 || B > ds->n_experts) return MOESPEC_ERR_INVALID_ARG;
+  if (policy == MOESPEC_SUBSTITUTE && B < ds->top_k) return MOESPEC_ERR_INVALID_ARG;
+  return MOESPEC_OK;
+}
+
+moespec_status from_hip(hipError_t e) { return e == hipSuccess ? MOESPEC_OK : MOESPEC_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t moespec_abi_version(void) { return 1; }
+
+const char *moespec_status_string(int32_t status) {
+  switch (status) {
+    case MOESPEC_OK: return "ok";
+    case MOESPEC_ERR_INVALID_ARG: return "invalid argument";
+    case MOESPEC_ERR_UNSUPPORTED_SHAPE: return "unsupported shape";
+    case MOESPEC_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MOESPEC_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+moespec_status moespec_check_desc(const moespec_desc *desc) { return check_desc(desc); }
+
+size_t moespec_workspace_bytes(const moespec_desc *desc, int32_t M_max) {
+  if (check_desc(desc) != MOESPEC_OK || M_max < 1 || M_max > kMaxTokens) return 0;
+  return carve_workspace(*desc, M_max, nullptr).bytes;
+}
+
+moespec_status moespec_route(const moespec_desc *desc, const moespec_weights *weights, const void *h, int32_t M,
+                             double *probs, int32_t *topk_ids, float *topk_w, void *ws, size_t ws_bytes,
+                             void *hip_stream) {
+  moespec_status s = check_common(desc, M, ws, ws_bytes);
+  if (s != MOESPEC_OK) return s;
+  if ((s = check_weights(weights, true, false)) != MOESPEC_OK) return s;
+  if (!h || !probs || !aligned16(h)) return MOESPEC_ERR_INVALID_ARG;
+  return from_hip(launch_route(*desc, *weights, h, M, probs, topk_ids, topk_w, static_cast<hipStream_t>(hip_stream)));
+}
+
+moespec_status moespec_budget(const moespec_desc *desc, const double *probs, int32_t M, int32_t B, int32_t policy,
+                              const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
+                              float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
+                              void *ws, size_t ws_bytes, void *hip_stream) {
+  moespec_status s = check_common(desc, M, ws, ws_bytes);
+  if (s != MOESPEC_OK) return s;
+  if ((s = check_budget(desc, B, policy)) != MOESPEC_OK) return s;
+  if (!probs || !tok_ids || !tok_w || !seg_expert || !seg_off || !perm) return MOESPEC_ERR_INVALID_ARG;
+  return from_hip(launch_budget(*desc, probs, M, B, policy, ext_shortlist, scores, budget_ids, tok_ids, tok_w,
+                                seg_expert, seg_off, perm, n_loaded, static_cast<hipStream_t>(hip_stream)));
+}
+
+moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weights *weights, const void *h, int32_t M,
+                                  int32_t n_seg, const int32_t *seg_expert, const int32_t *seg_off,
+                                  const int32_t *perm, const int32_t *tok_ids, const float *tok_w,
+                                  const void *residual, void *out, void *ws, size_t ws_bytes, void *hip_stream) {
+  moespec_status s = check_common(desc, M, ws, ws_bytes);
+  if (s != MOESPEC_OK) return s;
+  if ((s = check_weights(weights, false, true)) != MOESPEC_OK) return s;
+  if (n_seg < 1 || n_seg > desc->n_experts) return MOESPEC_ERR_INVALID_ARG;
+  if (!h || !seg_expert || !seg_off || !perm || !tok_ids || !tok_w || !out) return MOESPEC_ERR_INVALID_ARG;
+  if (!aligned16(h) || !aligned16(out) || (residual && !aligned16(residual))) return MOESPEC_ERR_INVALID_ARG;
+  Workspace w = carve_workspace(*desc, M, ws);
+  return from_hip(launch_expert_ffn(*desc, *weights, h, M, n_seg, seg_expert, seg_off, perm, tok_ids, tok_w, residual,
+                                    out, w.act, w.y, static_cast<hipStream_t>(hip_stream)));
+}
+
+moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_weights *weights, const void *h,
+                                     int32_t M, int32_t B, int32_t policy, const int32_t *ext_shortlist,
+                                     const void *residual, void *out, const moespec_taps *taps, void *ws,
+                                     size_t ws_bytes, void *hip_stream) {
+  moespec_status s = check_common(desc, M, ws, ws_bytes);
+  if (s != MOESPEC_OK) return s;
+  if ((s = check_weights(weights, true, true)) != MOESPEC_OK) return s;
+  if ((s = check_budget(desc, B, policy)) != MOESPEC_OK) return s;
+  if (!h || !out || !aligned16(h) || !aligned16(out) || (residual && !aligned16(residual)))
+    return MOESPEC_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  Workspace w = carve_workspace(*desc, M, ws);
+  // A tap replaces the workspace slot of the same intermediate, so it is written in place.
+  moespec_taps t = taps ? *taps : moespec_taps{};
+  double *probs = t.probs ? t.probs : w.probs;
+  int32_t *tok_ids = t.tok_ids ? t.tok_ids : w.tok_ids;
+  float *tok_w = t.tok_w ? t.tok_w : w.tok_w;
+  int32_t *seg_expert = t.seg_expert ? t.seg_expert : w.seg_expert;
+  int32_t *seg_off = t.seg_off ? t.seg_off : w.seg_off;
+  int32_t *perm = t.perm ? t.perm : w.perm;
+  hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, st);
+  if (e != hipSuccess) return MOESPEC_ERR_HIP;
+  e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, t.budget_ids, tok_ids, tok_w, seg_expert,
+                    seg_off, perm, t.n_loaded, st);
+  if (e != hipSuccess) return MOESPEC_ERR_HIP;
+  e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
+                        w.y, st);
+  return from_hip(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,170 @@
+// Stages 2-3 of Algorithm 1 without the expert maths: per-expert aggregation of routing
+// probability over the tree (Eq. (5)), top-B shortlist (Section 3.2), restriction of every token's
+// routing by truncation (Eq. (7)) or substitution (Eq. (8)), and the grouping of the surviving
+// (token, slot) pairs into per-expert segments.  All decisions in fp64, ties to the lowest id.
+#include "common.h"
+
+namespace moespec {
+
+constexpr int kBudgetThreads = 256;
+
+// One workgroup per tree token.  Every workgroup recomputes the (tiny) scores and shortlist so that
+// no grid-wide synchronisation is needed; workgroup 0 also writes them out.
+__global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
+    const double *__restrict__ probs, int M, int N, int k, int B, int policy, int renorm,
+    const int32_t *__restrict__ ext_shortlist, double *__restrict__ scores, int32_t *__restrict__ budget_ids,
+    int32_t *__restrict__ seg_expert, int32_t *__restrict__ tok_ids, float *__restrict__ tok_w) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  double *s = reinterpret_cast<double *>(smem);         // [N] aggregate scores
+  double *g = s + N;                                     // [N] this token's probabilities
+  double *wsel = g + N;                                  // [k]
+  int32_t *sel = reinterpret_cast<int32_t *>(wsel + k);  // [k]
+  int32_t *S = sel + k;                                  // [B] shortlist in rank order
+  uint8_t *inS = reinterpret_cast<uint8_t *>(S + B);     // [N] membership
+
+  const int t = blockIdx.x, tid = threadIdx.x;
+
+  for (int i = tid; i < N; i += blockDim.x) {
+    g[i] = probs[(size_t)t * N + i];
+    inS[i] = 0;
+  }
+  if (ext_shortlist == nullptr) {
+    // Eq. (5): s_i = sum over the M tree tokens of g_i(h_t), tokens in ascending order.
+    for (int i = tid; i < N; i += blockDim.x) {
+      double acc = 0.0;
+      for (int tt = 0; tt < M; ++tt) acc += probs[(size_t)tt * N + i];
+      s[i] = acc;
+    }
+    __syncthreads();
+    select_topk(s, nullptr, N, B, S);
+  } else {
+    for (int r = tid; r < B; r += blockDim.x) S[r] = ext_shortlist[r];
+    if (scores && t == 0) {
+      for (int i = tid; i < N; i += blockDim.x) {
+        double acc = 0.0;
+        for (int tt = 0; tt < M; ++tt) acc += probs[(size_t)tt * N + i];
+        s[i] = acc;
+      }
+    }
+  }
+  __syncthreads();
+  for (int r = tid; r < B; r += blockDim.x)
+    if ((uint32_t)S[r] < (uint32_t)N) inS[S[r]] = 1;  // ids outside [0, N) in an external shortlist are ignored
+  __syncthreads();
+
+  if (t == 0) {
+    for (int i = tid; i < N; i += blockDim.x) {
+      if (scores) scores[i] = s[i];
+      if (inS[i]) {  // position of expert i among the shortlisted experts in ascending id
+        int pos = 0;
+        for (int j = 0; j < i; ++j) pos += inS[j];
+        seg_expert[pos] = i;
+      }
+    }
+    int n_member = 0;  // < B only if an external shortlist repeats or misnames an expert
+    for (int j = 0; j < N; ++j) n_member += inS[j];
+    for (int r = tid; r < B; r += blockDim.x) {
+      if (r >= n_member) seg_expert[r] = -1;
+      if (budget_ids) budget_ids[r] = S[r];
+    }
+  }
+
+  if (policy == MOESPEC_TRUNCATE) {
+    // Natural top-k and its weights, then drop the slots outside S; kept weights are unchanged.
+    select_topk(g, nullptr, N, k, sel);
+    __syncthreads();
+    mixing_weights(g, sel, k, renorm, wsel);
+    __syncthreads();
+    for (int j = tid; j < k; j += blockDim.x) {
+      const bool keep = inS[sel[j]] != 0;
+      tok_ids[(size_t)t * k + j] = keep ? sel[j] : -1;
+      tok_w[(size_t)t * k + j] = keep ? (float)wsel[j] : 0.0f;
+    }
+  } else {
+    // Top-k inside S by g_i(h_t); weights over the constrained selection.  Slots stay unfilled (-1)
+    // only when an external shortlist names fewer than k valid experts.
+    for (int j = tid; j < k; j += blockDim.x) sel[j] = -1;
+    __syncthreads();
+    select_topk(g, inS, N, k, sel);
+    __syncthreads();
+    mixing_weights(g, sel, k, renorm, wsel);
+    __syncthreads();
+    for (int j = tid; j < k; j += blockDim.x) {
+      tok_ids[(size_t)t * k + j] = sel[j];
+      tok_w[(size_t)t * k + j] = (float)wsel[j];
+    }
+  }
+}
+
+// Groups the surviving (token, slot) pairs by expert: segment i holds the pairs routed to
+// seg_expert[i], tokens ascending.  One workgroup; one wave per segment, 64 tokens per ballot.
+__global__ __launch_bounds__(kBudgetThreads) void segments_kernel(const int32_t *__restrict__ tok_ids, int M, int k,
+                                                                  int B, const int32_t *__restrict__ seg_expert,
+                                                                  int32_t *__restrict__ seg_off,
+                                                                  int32_t *__restrict__ perm,
+                                                                  int32_t *__restrict__ n_loaded) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  int32_t *cnt = reinterpret_cast<int32_t *>(smem);  // [B] counts, then exclusive offsets
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwave = blockDim.x >> 6;
+
+  for (int i = wave; i < B; i += nwave) {
+    const int e = seg_expert[i];
+    int c = 0;
+    for (int t0 = 0; e >= 0 && t0 < M; t0 += kWave) {
+      const int t = t0 + lane;
+      bool has = false;
+      if (t < M)
+        for (int j = 0; j < k; ++j) has |= (tok_ids[(size_t)t * k + j] == e);
+      c += __popcll(__ballot(has));
+    }
+    if (lane == 0) cnt[i] = c;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0, loaded = 0;
+    for (int i = 0; i < B; ++i) {
+      const int c = cnt[i];
+      seg_off[i] = run;
+      cnt[i] = run;
+      run += c;
+      loaded += (c > 0);
+    }
+    seg_off[B] = run;
+    if (n_loaded) *n_loaded = loaded;
+    cnt[B] = run;
+  }
+  __syncthreads();
+  const int P = cnt[B];
+  for (int p = P + tid; p < M * k; p += blockDim.x) perm[p] = -1;
+  for (int i = wave; i < B; i += nwave) {
+    const int e = seg_expert[i];
+    int base = cnt[i];
+    for (int t0 = 0; e >= 0 && t0 < M; t0 += kWave) {
+      const int t = t0 + lane;
+      int slot = -1;
+      if (t < M)
+        for (int j = 0; j < k; ++j)
+          if (tok_ids[(size_t)t * k + j] == e) slot = j;
+      const unsigned long long mask = __ballot(slot >= 0);
+      if (slot >= 0) perm[base + __popcll(mask & ((1ull << lane) - 1ull))] = t * k + slot;
+      base += __popcll(mask);
+    }
+  }
+}
+
+hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
+                         const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
+                         float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
+                         hipStream_t st) {
+  const int N = ds.n_experts, k = ds.top_k;
+  const size_t smem = sizeof(double) * (2 * N + k) + sizeof(int32_t) * (k + B) + N;
+  budget_kernel<<<M, kBudgetThreads, smem, st>>>(probs, M, N, k, B, policy, ds.renorm, ext_shortlist, scores,
+                                                 budget_ids, seg_expert, tok_ids, tok_w);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  segments_kernel<<<1, kBudgetThreads, sizeof(int32_t) * (B + 1), st>>>(tok_ids, M, k, B, seg_expert, seg_off, perm,
+                                                                         n_loaded);
+  return hipGetLastError();
+}
+
+}  // namespace moespec

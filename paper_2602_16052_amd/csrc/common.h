@@ -1,0 +1,142 @@
+// Shared device/host helpers of the moespec kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moespec.h"
+
+namespace moespec {
+
+constexpr int kWave = 64;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// bfloat16 bit pattern <-> float.  Storage tensors hold raw uint16 patterns.
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+// Round-to-nearest-even; NaN stays NaN.
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float *p) { return *p; }
+  static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Elem<uint16_t> {
+  static __device__ __forceinline__ float load(const uint16_t *p) { return bf16_bits_to_float(*p); }
+  static __device__ __forceinline__ void store(uint16_t *p, float v) { *p = float_to_bf16_bits(v); }
+};
+
+// Ranking order used by every selection: larger value first, then lower index.
+__device__ __forceinline__ bool ranks_before(double vj, int j, double vi, int i) {
+  return vj > vi || (vj == vi && j < i);
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kWave);
+  return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v = fmax(v, __shfl_xor(v, s, kWave));
+  return v;
+}
+
+// Rank-count selection of the k best of v[0..n) restricted to candidates with member[i] != 0
+// (member == nullptr: all).  sel[r] receives the index with rank r < k.  Equivalent to sorting by
+// (value descending, index ascending) and keeping the first k.
+__device__ inline void select_topk(const double *v, const uint8_t *member, int n, int k, int32_t *sel) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    if (member && !member[i]) continue;
+    const double vi = v[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+      if (member && !member[j]) continue;
+      rank += ranks_before(v[j], j, vi, i) ? 1 : 0;
+    }
+    if (rank < k) sel[rank] = i;
+  }
+}
+
+// Mixing weights of the slots sel[0..k): raw g or g / sum over the slots (summed in slot order).
+// An unfilled slot (sel < 0) gets weight 0.
+__device__ inline void mixing_weights(const double *g, const int32_t *sel, int k, int renorm, double *w) {
+  if (threadIdx.x == 0) {
+    double denom = 0.0;
+    for (int s = 0; s < k; ++s)
+      if (sel[s] >= 0) denom += g[sel[s]];
+    for (int s = 0; s < k; ++s) w[s] = sel[s] < 0 ? 0.0 : (renorm ? g[sel[s]] / denom : g[sel[s]]);
+  }
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Workspace carve-up shared by all entry points (host).
+struct Workspace {
+  double *probs;      // [M, N]
+  double *scores;     // [N]
+  int32_t *budget_ids;  // [N]
+  int32_t *tok_ids;   // [M, k]
+  float *tok_w;       // [M, k]
+  int32_t *seg_expert;  // [N]
+  int32_t *seg_off;   // [N + 1]
+  int32_t *perm;      // [M * k]
+  int32_t *n_loaded;  // [1]
+  void *act;          // [M * k, F] dtype
+  float *y;           // [M * k, d]
+  size_t bytes;
+};
+
+inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) {
+  Workspace w;
+  size_t off = 0;
+  char *b = static_cast<char *>(base);
+  auto take = [&](size_t n) {
+    void *p = b ? b + off : nullptr;
+    off += align_up(n, 256);
+    return p;
+  };
+  const int64_t N = ds.n_experts, k = ds.top_k, F = ds.d_ff, d = ds.d;
+  const size_t es = ds.dtype == MOESPEC_BF16 ? 2 : 4;
+  w.probs = static_cast<double *>(take(sizeof(double) * M * N));
+  w.scores = static_cast<double *>(take(sizeof(double) * N));
+  w.budget_ids = static_cast<int32_t *>(take(sizeof(int32_t) * N));
+  w.tok_ids = static_cast<int32_t *>(take(sizeof(int32_t) * M * k));
+  w.tok_w = static_cast<float *>(take(sizeof(float) * M * k));
+  w.seg_expert = static_cast<int32_t *>(take(sizeof(int32_t) * N));
+  w.seg_off = static_cast<int32_t *>(take(sizeof(int32_t) * (N + 1)));
+  w.perm = static_cast<int32_t *>(take(sizeof(int32_t) * M * k));
+  w.n_loaded = static_cast<int32_t *>(take(sizeof(int32_t)));
+  w.act = take(es * M * k * F);
+  w.y = static_cast<float *>(take(sizeof(float) * M * k * d));
+  w.bytes = off;
+  return w;
+}
+
+// Launchers (defined in the .hip files).  Each returns hipGetLastError() after its launches.
+hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *probs,
+                        int32_t *topk_ids, float *topk_w, hipStream_t st);
+hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
+                         const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
+                         float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
+                         hipStream_t st);
+hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
+                             const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
+                             const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
+                             float *y, hipStream_t st);
+
+}  // namespace moespec

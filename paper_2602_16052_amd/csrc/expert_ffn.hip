@@ -1,0 +1,307 @@
+// The expert networks over the loaded experts (Eq. (2)/(7)/(8)) and the weighted combine.
+//
+// E_i(x) = W_down,i ( silu(W_gate,i x) * (W_up,i x) ) is evaluated per segment (one expert, the
+// hidden rows of its (token, slot) pairs) in two passes over that expert's weights:
+//   pass 1  act[p, :] = silu(W_gate x_p) * (W_up x_p)        streams W_gate,i and W_up,i once
+//   pass 2  y[pair, :] = W_down act[p, :]                    streams W_down,i once
+// and a final combine adds the k weighted rows of every token in slot order (deterministic).
+//
+// bf16 path: the weight rows are the MFMA "A" side and go from global memory straight into the
+// v_mfma_f32_16x16x32_bf16 operand layout (lane l holds 8 consecutive K elements of row l%16,
+// K group l/16), so every weight byte is loaded exactly once by exactly one lane; tokens are the
+// "B" side (16 per tile, up to 8 tiles per pass) and come from the small, cache-resident hidden /
+// activation rows.  Work is cut into equal-byte items (32 weight rows x K per wave) so that the
+// byte load per compute unit is balanced however uneven the segment sizes are.
+#include "common.h"
+
+namespace moespec {
+
+constexpr int kFfnThreads = 256;
+constexpr int kFfnWaves = kFfnThreads / kWave;
+constexpr int kMaxTiles = 8;  // token tiles of 16 per pass over the weights
+
+// A segment is processed only if it names a real expert and lies inside the pair table; pair
+// indices are clamped into [0, M*k) so that malformed tables cannot address outside the buffers.
+__device__ __forceinline__ bool segment_ok(int e, int beg, int m, int M, int N, int k) {
+  return e >= 0 && e < N && m > 0 && beg >= 0 && (long long)beg + m <= (long long)M * k;
+}
+__device__ __forceinline__ int pair_index(const int32_t *perm, int pos, int M, int k) {
+  const int q = perm[pos];
+  return q < 0 ? 0 : (q >= M * k ? M * k - 1 : q);
+}
+
+__device__ __forceinline__ bf16x8 ld_frag(const uint16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
+
+// acc0[j] += A0 . B_j, acc1[j] += A1 . B_j over K, for NT token tiles; U K-steps of 32 per stage,
+// two register stages so that the next stage's loads are in flight during the current MFMAs.
+// a0/a1/bp[] are per-lane pointers (already offset by the lane's row and K group).  K % (32 U) == 0.
+template <int NT, int U>
+__device__ __forceinline__ void stream_rows(const uint16_t *a0, const uint16_t *a1, const uint16_t *const (&bp)[NT],
+                                            int K, f32x4 (&acc0)[NT], f32x4 (&acc1)[NT]) {
+  bf16x8 A0[2][U], A1[2][U], Bf[2][U][NT];
+  auto load = [&](int st, int k0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      A0[st][u] = ld_frag(a0 + k0 + 32 * u);
+      A1[st][u] = ld_frag(a1 + k0 + 32 * u);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) Bf[st][u][j] = ld_frag(bp[j] + k0 + 32 * u);
+  };
+  auto compute = [&](int st) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        acc0[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A0[st][u], Bf[st][u][j], acc0[j], 0, 0, 0);
+        acc1[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A1[st][u], Bf[st][u][j], acc1[j], 0, 0, 0);
+      }
+  };
+  constexpr int KS = 32 * U;
+  load(0, 0);
+  for (int k0 = 0; k0 < K; k0 += 2 * KS) {
+    if (k0 + KS < K) load(1, k0 + KS);
+    compute(0);
+    if (k0 + 2 * KS < K) load(0, k0 + 2 * KS);
+    if (k0 + KS < K) compute(1);
+  }
+}
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+
+// ---- pass 1 (bf16): gate/up projections + SwiGLU ---------------------------------------------
+template <int NT, int U>
+__device__ __forceinline__ void gateup_tiles(const uint16_t *a0, const uint16_t *a1, const uint16_t *__restrict__ h,
+                                             const int32_t *__restrict__ perm, int M, int k, int d, int F, int beg,
+                                             int c0, int m, int f0, uint16_t *__restrict__ act) {
+  const int lane = threadIdx.x & 63, col = lane & 15, kg = lane >> 4;
+  const uint16_t *bp[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    int p = c0 + j * 16 + col;
+    p = p < m ? p : m - 1;  // pad columns repeat the last token; their results are never stored
+    const int tok = pair_index(perm, beg + p, M, k) / k;
+    bp[j] = h + (size_t)tok * d + kg * 8;
+  }
+  f32x4 accg[NT], accu[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) accg[j] = accu[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  stream_rows<NT, U>(a0, a1, bp, d, accg, accu);
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int p = c0 + j * 16 + col;
+    if (p < m) {
+      uint16_t o[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[i] = float_to_bf16_bits(silu_f(accg[j][i]) * accu[j][i]);
+      uint2 pk;
+      pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
+      pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
+      *reinterpret_cast<uint2 *>(act + (size_t)(beg + p) * F + f0 + 4 * kg) = pk;
+    }
+  }
+}
+
+template <int U>
+__global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_bf16_kernel(
+    const uint16_t *__restrict__ h, const uint16_t *__restrict__ w_gate, const uint16_t *__restrict__ w_up,
+    const int32_t *__restrict__ seg_expert, const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm,
+    int M, int N, int k, int d, int F, uint16_t *__restrict__ act) {
+  const int seg = blockIdx.y;
+  const int e = seg_expert[seg];
+  const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
+  if (!segment_ok(e, beg, m, M, N, k)) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int f0 = (blockIdx.x * kFfnWaves + wave) * 16;
+  if (f0 >= F) return;
+  const size_t row = (size_t)e * F + f0 + (lane & 15);
+  const uint16_t *a0 = w_gate + row * d + (lane >> 4) * 8;
+  const uint16_t *a1 = w_up + row * d + (lane >> 4) * 8;
+  constexpr int U4 = U > 2 ? 2 : U;
+  for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
+    const int mc = m - c0;
+    if (mc <= 16) gateup_tiles<1, U>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, act);
+    else if (mc <= 32) gateup_tiles<2, U>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, act);
+    else if (mc <= 64) gateup_tiles<4, U4>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, act);
+    else gateup_tiles<8, 1>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, act);
+  }
+}
+
+// ---- pass 2 (bf16): down projection, rows scattered to their (token, slot) position -----------
+template <int NT, int U>
+__device__ __forceinline__ void down_tiles(const uint16_t *a0, const uint16_t *a1, const uint16_t *__restrict__ act,
+                                           const int32_t *__restrict__ perm, int M, int k, int d, int F, int beg, int c0,
+                                           int m, int j0, float *__restrict__ y) {
+  const int lane = threadIdx.x & 63, col = lane & 15, kg = lane >> 4;
+  const uint16_t *bp[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    int p = c0 + j * 16 + col;
+    p = p < m ? p : m - 1;
+    bp[j] = act + (size_t)(beg + p) * F + kg * 8;
+  }
+  f32x4 acc0[NT], acc1[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) acc0[j] = acc1[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  stream_rows<NT, U>(a0, a1, bp, F, acc0, acc1);
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int p = c0 + j * 16 + col;
+    if (p < m) {
+      float *dst = y + (size_t)pair_index(perm, beg + p, M, k) * d + j0 + 4 * kg;
+      *reinterpret_cast<f32x4 *>(dst) = acc0[j];
+      *reinterpret_cast<f32x4 *>(dst + 16) = acc1[j];
+    }
+  }
+}
+
+template <int U>
+__global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_bf16_kernel(
+    const uint16_t *__restrict__ act, const uint16_t *__restrict__ w_down, const int32_t *__restrict__ seg_expert,
+    const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm, int M, int N, int k, int d, int F,
+    float *__restrict__ y) {
+  const int seg = blockIdx.y;
+  const int e = seg_expert[seg];
+  const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
+  if (!segment_ok(e, beg, m, M, N, k)) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int j0 = (blockIdx.x * kFfnWaves + wave) * 32;
+  if (j0 >= d) return;
+  const uint16_t *a0 = w_down + ((size_t)e * d + j0 + (lane & 15)) * F + (lane >> 4) * 8;
+  const uint16_t *a1 = a0 + (size_t)16 * F;
+  constexpr int U4 = U > 2 ? 2 : U;
+  for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
+    const int mc = m - c0;
+    if (mc <= 16) down_tiles<1, U>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, y);
+    else if (mc <= 32) down_tiles<2, U>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, y);
+    else if (mc <= 64) down_tiles<4, U4>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, y);
+    else down_tiles<8, 1>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, y);
+  }
+}
+
+// ---- fp32 path: one wave per weight row, lanes stride K (correctness path for small layers) ----
+__global__ __launch_bounds__(kFfnThreads) void ffn_gateup_f32_kernel(
+    const float *__restrict__ h, const float *__restrict__ w_gate, const float *__restrict__ w_up,
+    const int32_t *__restrict__ seg_expert, const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm,
+    int M, int N, int k, int d, int F, float *__restrict__ act) {
+  const int seg = blockIdx.y;
+  const int e = seg_expert[seg];
+  const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
+  if (!segment_ok(e, beg, m, M, N, k)) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int f = blockIdx.x * kFfnWaves + wave;
+  if (f >= F) return;
+  const float *wg = w_gate + ((size_t)e * F + f) * d;
+  const float *wu = w_up + ((size_t)e * F + f) * d;
+  for (int p = 0; p < m; ++p) {
+    const float *x = h + (size_t)(pair_index(perm, beg + p, M, k) / k) * d;
+    float g = 0.f, u = 0.f;
+    for (int j = lane; j < d; j += kWave) {
+      const float xv = x[j];
+      g = fmaf(wg[j], xv, g);
+      u = fmaf(wu[j], xv, u);
+    }
+    g = wave_sum(g);
+    u = wave_sum(u);
+    if (lane == 0) act[(size_t)(beg + p) * F + f] = g / (1.0f + expf(-g)) * u;
+  }
+}
+
+__global__ __launch_bounds__(kFfnThreads) void ffn_down_f32_kernel(
+    const float *__restrict__ act, const float *__restrict__ w_down, const int32_t *__restrict__ seg_expert,
+    const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm, int M, int N, int k, int d, int F,
+    float *__restrict__ y) {
+  const int seg = blockIdx.y;
+  const int e = seg_expert[seg];
+  const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
+  if (!segment_ok(e, beg, m, M, N, k)) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int j = blockIdx.x * kFfnWaves + wave;
+  if (j >= d) return;
+  const float *wd = w_down + ((size_t)e * d + j) * F;
+  for (int p = 0; p < m; ++p) {
+    const float *a = act + (size_t)(beg + p) * F;
+    float acc = 0.f;
+    for (int f = lane; f < F; f += kWave) acc = fmaf(wd[f], a[f], acc);
+    acc = wave_sum(acc);
+    if (lane == 0) y[(size_t)pair_index(perm, beg + p, M, k) * d + j] = acc;
+  }
+}
+
+// ---- combine: out[t] = residual[t] + sum over surviving slots (slot order) of w * y[t*k+slot] ---
+template <typename T>
+__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ y, const int32_t *__restrict__ tok_ids,
+                                                      const float *__restrict__ tok_w, const T *__restrict__ residual,
+                                                      int k, int d, T *__restrict__ out) {
+  const int t = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= d) return;
+  float acc = residual ? Elem<T>::load(residual + (size_t)t * d + j) : 0.0f;
+  for (int s = 0; s < k; ++s) {
+    if (tok_ids[(size_t)t * k + s] >= 0) acc = fmaf(tok_w[(size_t)t * k + s], y[((size_t)t * k + s) * d + j], acc);
+  }
+  Elem<T>::store(out + (size_t)t * d + j, acc);
+}
+
+template <int U>
+static hipError_t launch_bf16(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
+                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm, void *act,
+                              float *y, int pass, hipStream_t st) {
+  const int d = ds.d, F = ds.d_ff, k = ds.top_k;
+  if (pass == 1) {
+    dim3 grid((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg);
+    ffn_gateup_bf16_kernel<U><<<grid, kFfnThreads, 0, st>>>(
+        static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(wt.w_gate),
+        static_cast<const uint16_t *>(wt.w_up), seg_expert, seg_off, perm, M, ds.n_experts, k, d, F,
+        static_cast<uint16_t *>(act));
+  } else {
+    dim3 grid((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg);
+    ffn_down_bf16_kernel<U><<<grid, kFfnThreads, 0, st>>>(static_cast<const uint16_t *>(act),
+                                                          static_cast<const uint16_t *>(wt.w_down), seg_expert,
+                                                          seg_off, perm, M, ds.n_experts, k, d, F, y);
+  }
+  return hipGetLastError();
+}
+
+static int pick_unroll(int K) { return K % 128 == 0 ? 4 : (K % 64 == 0 ? 2 : 1); }
+
+hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
+                             const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
+                             const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
+                             float *y, hipStream_t st) {
+  const int d = ds.d, F = ds.d_ff, k = ds.top_k;
+  hipError_t e;
+  if (ds.dtype == MOESPEC_BF16) {
+    for (int pass = 1; pass <= 2; ++pass) {
+      switch (pick_unroll(pass == 1 ? d : F)) {
+        case 4: e = launch_bf16<4>(ds, wt, h, M, n_seg, seg_expert, seg_off, perm, act, y, pass, st); break;
+        case 2: e = launch_bf16<2>(ds, wt, h, M, n_seg, seg_expert, seg_off, perm, act, y, pass, st); break;
+        default: e = launch_bf16<1>(ds, wt, h, M, n_seg, seg_expert, seg_off, perm, act, y, pass, st); break;
+      }
+      if (e != hipSuccess) return e;
+    }
+    dim3 cgrid((d + 255) / 256, M);
+    combine_kernel<uint16_t><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const uint16_t *>(residual), k, d,
+                                                    static_cast<uint16_t *>(out));
+    return hipGetLastError();
+  }
+  dim3 g1((F + kFfnWaves - 1) / kFfnWaves, n_seg);
+  ffn_gateup_f32_kernel<<<g1, kFfnThreads, 0, st>>>(static_cast<const float *>(h),
+                                                    static_cast<const float *>(wt.w_gate),
+                                                    static_cast<const float *>(wt.w_up), seg_expert, seg_off, perm, M,
+                                                    ds.n_experts, k, d, F, static_cast<float *>(act));
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  dim3 g2((d + kFfnWaves - 1) / kFfnWaves, n_seg);
+  ffn_down_f32_kernel<<<g2, kFfnThreads, 0, st>>>(static_cast<const float *>(act),
+                                                  static_cast<const float *>(wt.w_down), seg_expert, seg_off, perm, M,
+                                                  ds.n_experts, k, d, F, y);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  dim3 cgrid((d + 255) / 256, M);
+  combine_kernel<float><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const float *>(residual), k, d,
+                                               static_cast<float *>(out));
+  return hipGetLastError();
+}
+
+}  // namespace moespec

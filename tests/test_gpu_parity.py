@@ -1,0 +1,174 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer outputs (shortlist, routing ids, segments, permutation) must be bit-exact;
+layer outputs within max-abs 2e-2 (bf16) / 1e-5 (fp32), absolute and relative to max|oracle|."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moespec_oracle as O
+from paper_2602_16052_amd import binding as mb
+from paper_2602_16052_amd import workloads as wl
+
+from gpu_common import (TOL, assert_out_close, assert_routing_equal, desc_of, oracle_weights, out_to_numpy,
+                        to_device, upload_weights)
+
+pytestmark = pytest.mark.gpu
+
+SMALL = {
+    # name: config  (shapes chosen to span several 16-token tiles, ragged tails and every K-unroll variant)
+    "s_bf16_a": wl.small_config("s_bf16_a", "bf16", d=256, n_experts=16, top_k=4, d_ff=192, M=37, budgets=(4, 8, 16)),
+    "s_bf16_k1": wl.small_config("s_bf16_k1", "bf16", d=96, n_experts=8, top_k=1, d_ff=160, M=21, budgets=(1, 3, 8),
+                                 renorm=False),
+    "s_bf16_big_seg": wl.small_config("s_bf16_big_seg", "bf16", d=128, n_experts=4, top_k=2, d_ff=64, M=300,
+                                      budgets=(2, 4), bias_alpha=0.3),
+    "s_bf16_m1": wl.small_config("s_bf16_m1", "bf16", d=64, n_experts=8, top_k=2, d_ff=32, M=1, budgets=(2, 8)),
+    "s_bf16_n100": wl.small_config("s_bf16_n100", "bf16", d=320, n_experts=100, top_k=6, d_ff=96, M=70,
+                                   budgets=(6, 40, 100), bias_alpha=1.0, renorm=False),
+    "s_f32_a": wl.small_config("s_f32_a", "f32", d=100, n_experts=12, top_k=3, d_ff=52, M=19, budgets=(3, 6, 12)),
+    "tiny_f32": wl.CONFIGS["tiny_f32"],
+}
+
+
+def make_case(cfg):
+    h = wl.hidden_states(cfg)
+    W = wl.layer_weights(cfg)
+    return h, W
+
+
+@pytest.fixture(scope="module")
+def cases():
+    cache = {}
+
+    def get(name):
+        if name not in cache:
+            cfg = SMALL[name]
+            h, W = make_case(cfg)
+            desc = desc_of(cfg)
+            cache[name] = dict(cfg=cfg, h=h, W=W, desc=desc, h_d=to_device(h), W_d=upload_weights(W),
+                               h_o=wl.as_f32(h), W_o=oracle_weights(W), ws=mb.alloc_workspace(desc, cfg.M))
+        return cache[name]
+    return get
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_route_parity(cases, name):
+    c = cases(name)
+    cfg = c["cfg"]
+    r = mb.moespec_route(c["desc"], c["W_d"], c["h_d"], c["ws"])
+    torch.cuda.synchronize()
+    g, ids, w = O.route(c["h_o"], c["W_o"]["w_router"], c["W_o"]["b_router"], cfg.top_k, cfg.renorm)
+    np.testing.assert_allclose(r["probs"].cpu().numpy(), g, rtol=1e-11, atol=1e-300)
+    assert np.array_equal(r["topk_ids"].cpu().numpy(), ids)
+    np.testing.assert_allclose(r["topk_w"].cpu().numpy(), w, rtol=1e-6)
+
+
+@pytest.mark.parametrize("policy", [mb.TRUNCATE, mb.SUBSTITUTE])
+@pytest.mark.parametrize("name", list(SMALL))
+def test_layer_forward_parity_small(cases, name, policy):
+    c = cases(name)
+    cfg = c["cfg"]
+    for B in cfg.budgets:
+        if policy == mb.SUBSTITUTE and B < cfg.top_k:
+            continue
+        print(f"case {name} B={B} policy={policy}", flush=True)
+        out, taps = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], B, policy, c["ws"], taps=True)
+        torch.cuda.synchronize()
+        ref = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, B, policy)
+        assert_routing_equal(taps, ref, B)
+        assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)
+        if policy == mb.TRUNCATE:
+            dropped = [t for t in range(cfg.M) if np.all(ref["tok_ids"][t] < 0)]
+            if dropped:
+                assert torch.all(out[dropped] == 0), "tokens without a surviving expert must get exact zeros"
+
+
+@pytest.mark.parametrize("name", ["s_bf16_a", "s_f32_a"])
+def test_stage_calls_compose_to_the_fused_call(cases, name):
+    """route -> budget -> expert_ffn through their own entry points equals layer_forward bit for bit."""
+    c = cases(name)
+    cfg = c["cfg"]
+    B = cfg.budgets[1]
+    for policy in (mb.TRUNCATE, mb.SUBSTITUTE):
+        r = mb.moespec_route(c["desc"], c["W_d"], c["h_d"], c["ws"])
+        b = mb.moespec_budget(c["desc"], r["probs"], B, policy, c["ws"])
+        out = mb.moespec_expert_ffn(c["desc"], c["W_d"], c["h_d"], b["seg_expert"], b["seg_off"], b["perm"],
+                                    b["tok_ids"], b["tok_w"], c["ws"])
+        out2, taps = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], B, policy, c["ws"], taps=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2)
+        for key in ("tok_ids", "tok_w", "seg_expert", "seg_off", "perm", "budget_ids", "scores", "n_loaded"):
+            assert torch.equal(b[key], taps[key]), key
+        if policy == mb.TRUNCATE:
+            # Eq. (7): kept weights are the natural top-k weights, bit for bit.
+            keep = b["tok_ids"] >= 0
+            assert torch.equal(b["tok_ids"][keep], r["topk_ids"][keep])
+            assert torch.equal(b["tok_w"][keep], r["topk_w"][keep])
+            assert torch.all(b["tok_w"][~keep] == 0)
+
+
+def test_full_budget_is_the_unbudgeted_layer(cases):
+    """B = N: both policies reproduce the natural routing and Eq. (2); the loaded set is the union of Eq. (3)."""
+    c = cases("s_bf16_a")
+    cfg = c["cfg"]
+    r = mb.moespec_route(c["desc"], c["W_d"], c["h_d"], c["ws"])
+    outs = []
+    for policy in (mb.TRUNCATE, mb.SUBSTITUTE):
+        out, taps = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], cfg.n_experts, policy, c["ws"], taps=True)
+        torch.cuda.synchronize()
+        assert torch.equal(taps["tok_ids"], r["topk_ids"])
+        assert torch.equal(taps["tok_w"], r["topk_w"])
+        union = O.expert_union(r["topk_ids"].cpu().numpy())
+        assert int(taps["n_loaded"][0]) == len(union)
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1])
+    ref = O.unbudgeted_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm)
+    assert_out_close(out_to_numpy(outs[0]), ref, cfg.dtype)
+
+
+def test_external_shortlist_and_residual(cases):
+    c = cases("s_bf16_a")
+    cfg = c["cfg"]
+    ext = [11, 2, 7, 5, 14, 0]
+    ext_d = torch.tensor(ext, dtype=torch.int32, device="cuda")
+    resid = torch.randn(cfg.M, cfg.d, generator=torch.Generator().manual_seed(1)).to(torch.bfloat16).cuda()
+    for policy in (mb.TRUNCATE, mb.SUBSTITUTE):
+        out, taps = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], len(ext), policy, c["ws"],
+                                             ext_shortlist=ext_d, residual=resid, taps=True)
+        torch.cuda.synchronize()
+        ref = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, len(ext), policy, ext_shortlist=ext)
+        assert_routing_equal(taps, ref, len(ext))
+        want = ref["out"] + resid.float().cpu().numpy().astype(np.float64)
+        assert_out_close(out_to_numpy(out), want, cfg.dtype)
+
+
+def test_repeated_calls_are_bit_identical(cases):
+    c = cases("s_bf16_n100")
+    cfg = c["cfg"]
+    first = None
+    for _ in range(5):
+        out, taps = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], 40, mb.SUBSTITUTE, c["ws"], taps=True)
+        torch.cuda.synchronize()
+        snap = [out.clone()] + [taps[k].clone() for k in sorted(taps)]
+        if first is None:
+            first = snap
+        else:
+            for a, b in zip(first, snap):
+                assert torch.equal(a, b)
+
+
+def test_ties_go_to_the_lowest_id_on_the_gpu():
+    """Duplicated router rows give exactly equal probabilities: ranking must break ties by id."""
+    cfg = wl.small_config("ties", "bf16", d=64, n_experts=8, top_k=3, d_ff=32, M=9, budgets=(4,))
+    h, W = make_case(cfg)
+    W["w_router"][2] = W["w_router"][0]
+    W["w_router"][5] = W["w_router"][0]
+    W["w_router"][4] = W["w_router"][1]
+    W["b_router"][:] = 0
+    desc = desc_of(cfg)
+    ws = mb.alloc_workspace(desc, cfg.M)
+    for policy in (mb.TRUNCATE, mb.SUBSTITUTE):
+        out, taps = mb.moespec_layer_forward(desc, upload_weights(W), to_device(h), 4, policy, ws, taps=True)
+        torch.cuda.synchronize()
+        ref = O.layer_forward(wl.as_f32(h), oracle_weights(W), cfg.top_k, cfg.renorm, 4, policy)
+        assert_routing_equal(taps, ref, 4)
+        assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)
