@@ -6,12 +6,18 @@
 //   pass 2  y[pair, :] = W_down act[p, :]                    streams W_down,i once
 // and a final combine adds the k weighted rows of every token in slot order (deterministic).
 //
-// bf16 path: the weight rows are the MFMA "A" side and go from global memory straight into the
-// v_mfma_f32_16x16x32_bf16 operand layout (lane l holds 8 consecutive K elements of row l%16,
-// K group l/16), so every weight byte is loaded exactly once by exactly one lane; tokens are the
-// "B" side (16 per tile, up to 8 tiles per pass) and come from the small, cache-resident hidden /
-// activation rows.  Work is cut into equal-byte items (32 weight rows x K per wave) so that the
-// byte load per compute unit is balanced however uneven the segment sizes are.
+// bf16 path.  Weight rows are the MFMA "A" side (v_mfma_f32_16x16x32_bf16), tokens the "B" side
+// (16 per tile, up to 8 tiles per pass, so a segment of up to 128 pairs reads its expert once).
+// Work is cut into equal-byte items: a workgroup of 4 waves takes 128 weight rows (32 per wave)
+// of one expert and walks K in chunks; however uneven the segment sizes, every compute unit
+// streams the same number of weight bytes.  Per chunk each wave loads its rows with fully
+// coalesced 16-byte loads, parks them in a wave-private, XOR-swizzled LDS tile and reads them
+// back in MFMA operand layout; the token chunk is loaded once per workgroup into a shared,
+// double-buffered LDS tile.  (Loading operands from global memory directly in MFMA layout costs a
+// cache-line lookup per lane and saturates the texture-address path long before HBM.)
+// Workgroups start their K walk at staggered offsets: weight rows are a power-of-two stride
+// apart, and equal offsets would pile the concurrent reads onto the same memory channels.
+// Shapes whose K is not a multiple of 128 take a simpler direct-load variant of the same tiling.
 #include "common.h"
 
 namespace moespec {
@@ -35,9 +41,12 @@ __device__ __forceinline__ bf16x8 ld_frag(const uint16_t *p) { return *reinterpr
 // acc0[j] += A0 . B_j, acc1[j] += A1 . B_j over K, for NT token tiles; U K-steps of 32 per stage,
 // two register stages so that the next stage's loads are in flight during the current MFMAs.
 // a0/a1/bp[] are per-lane pointers (already offset by the lane's row and K group).  K % (32 U) == 0.
+// The walk over K starts at element ks (a multiple of 32 U) and wraps: waves that start at
+// different offsets spread the concurrent row reads over the memory channels (rows of a weight
+// matrix are a power-of-two stride apart, so equal offsets would pile onto the same channels).
 template <int NT, int U>
 __device__ __forceinline__ void stream_rows(const uint16_t *a0, const uint16_t *a1, const uint16_t *const (&bp)[NT],
-                                            int K, f32x4 (&acc0)[NT], f32x4 (&acc1)[NT]) {
+                                            int K, int ks, f32x4 (&acc0)[NT], f32x4 (&acc1)[NT]) {
   bf16x8 A0[2][U], A1[2][U], Bf[2][U][NT];
   auto load = [&](int st, int k0) {
 #pragma unroll
@@ -60,14 +69,23 @@ __device__ __forceinline__ void stream_rows(const uint16_t *a0, const uint16_t *
       }
   };
   constexpr int KS = 32 * U;
-  load(0, 0);
-  for (int k0 = 0; k0 < K; k0 += 2 * KS) {
-    if (k0 + KS < K) load(1, k0 + KS);
+  const int nst = K / KS;
+  int k = (ks / KS) * KS;
+  load(0, k);
+  for (int i = 0; i < nst; i += 2) {
+    int k1 = k + KS;
+    k1 = k1 >= K ? k1 - K : k1;
+    if (i + 1 < nst) load(1, k1);
     compute(0);
-    if (k0 + 2 * KS < K) load(0, k0 + 2 * KS);
-    if (k0 + KS < K) compute(1);
+    k = k1 + KS;
+    k = k >= K ? k - K : k;
+    if (i + 2 < nst) load(0, k);
+    if (i + 1 < nst) compute(1);
   }
 }
+
+// Start offset (elements) of a wave's walk over K: 128 elements (256 bytes) apart for consecutive waves.
+__device__ __forceinline__ int k_stagger(int wave_id, int K) { return (int)(((long long)wave_id * 128) % K); }
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
@@ -75,7 +93,7 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 template <int NT, int U>
 __device__ __forceinline__ void gateup_tiles(const uint16_t *a0, const uint16_t *a1, const uint16_t *__restrict__ h,
                                              const int32_t *__restrict__ perm, int M, int k, int d, int F, int beg,
-                                             int c0, int m, int f0, uint16_t *__restrict__ act) {
+                                             int c0, int m, int f0, int ks, uint16_t *__restrict__ act) {
   const int lane = threadIdx.x & 63, col = lane & 15, kg = lane >> 4;
   const uint16_t *bp[NT];
 #pragma unroll
@@ -88,7 +106,7 @@ __device__ __forceinline__ void gateup_tiles(const uint16_t *a0, const uint16_t 
   f32x4 accg[NT], accu[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) accg[j] = accu[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_rows<NT, U>(a0, a1, bp, d, accg, accu);
+  stream_rows<NT, U>(a0, a1, bp, d, ks, accg, accu);
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
     const int p = c0 + j * 16 + col;
@@ -119,13 +137,14 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_bf16_kernel(
   const size_t row = (size_t)e * F + f0 + (lane & 15);
   const uint16_t *a0 = w_gate + row * d + (lane >> 4) * 8;
   const uint16_t *a1 = w_up + row * d + (lane >> 4) * 8;
+  const int ks = k_stagger((blockIdx.y * gridDim.x + blockIdx.x) * kFfnWaves + wave, d);
   constexpr int U4 = U > 2 ? 2 : U;
   for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
     const int mc = m - c0;
-    if (mc <= 16) gateup_tiles<1, U>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, act);
-    else if (mc <= 32) gateup_tiles<2, U>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, act);
-    else if (mc <= 64) gateup_tiles<4, U4>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, act);
-    else gateup_tiles<8, 1>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, act);
+    if (mc <= 16) gateup_tiles<1, U>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, ks, act);
+    else if (mc <= 32) gateup_tiles<2, U>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, ks, act);
+    else if (mc <= 64) gateup_tiles<4, U4>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, ks, act);
+    else gateup_tiles<8, 1>(a0, a1, h, perm, M, k, d, F, beg, c0, m, f0, ks, act);
   }
 }
 
@@ -133,7 +152,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_bf16_kernel(
 template <int NT, int U>
 __device__ __forceinline__ void down_tiles(const uint16_t *a0, const uint16_t *a1, const uint16_t *__restrict__ act,
                                            const int32_t *__restrict__ perm, int M, int k, int d, int F, int beg, int c0,
-                                           int m, int j0, float *__restrict__ y) {
+                                           int m, int j0, int ks, float *__restrict__ y) {
   const int lane = threadIdx.x & 63, col = lane & 15, kg = lane >> 4;
   const uint16_t *bp[NT];
 #pragma unroll
@@ -145,7 +164,7 @@ __device__ __forceinline__ void down_tiles(const uint16_t *a0, const uint16_t *a
   f32x4 acc0[NT], acc1[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) acc0[j] = acc1[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_rows<NT, U>(a0, a1, bp, F, acc0, acc1);
+  stream_rows<NT, U>(a0, a1, bp, F, ks, acc0, acc1);
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
     const int p = c0 + j * 16 + col;
@@ -171,13 +190,218 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_bf16_kernel(
   if (j0 >= d) return;
   const uint16_t *a0 = w_down + ((size_t)e * d + j0 + (lane & 15)) * F + (lane >> 4) * 8;
   const uint16_t *a1 = a0 + (size_t)16 * F;
+  const int ks = k_stagger((blockIdx.y * gridDim.x + blockIdx.x) * kFfnWaves + wave, F);
   constexpr int U4 = U > 2 ? 2 : U;
   for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
     const int mc = m - c0;
-    if (mc <= 16) down_tiles<1, U>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, y);
-    else if (mc <= 32) down_tiles<2, U>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, y);
-    else if (mc <= 64) down_tiles<4, U4>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, y);
-    else down_tiles<8, 1>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, y);
+    if (mc <= 16) down_tiles<1, U>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, ks, y);
+    else if (mc <= 32) down_tiles<2, U>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, ks, y);
+    else if (mc <= 64) down_tiles<4, U4>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, ks, y);
+    else down_tiles<8, 1>(a0, a1, act, perm, M, k, d, F, beg, c0, m, j0, ks, y);
+  }
+}
+
+// ---- LDS-tiled bf16 passes (K % 128 == 0) --------------------------------------------------------
+// Geometry of one K chunk: U MFMA K-steps of 32 elements; a row of the chunk is RB = 64 U bytes =
+// CPR = 4 U pieces of 16 bytes.  Piece c of row r sits at LDS offset r*RB + ((c ^ (r & (CPR-1))) * 16):
+// 8 consecutive lanes then touch 8 different 16-byte bank groups both when a row is written
+// (lanes along the row) and when it is read in operand layout (lanes across rows).
+template <int U>
+struct Chunk {
+  static constexpr int KC = 32 * U;        // elements per chunk
+  static constexpr int CPR = 4 * U;        // 16-byte pieces per row
+  static constexpr int RB = 64 * U;        // bytes per row
+  static constexpr int RPI = 64 / CPR;     // rows covered by one wave-wide load
+  static constexpr int TILE = 16 * RB;     // bytes of a 16-row tile
+  static __device__ __forceinline__ int swz(int row, int piece) { return row * RB + ((piece ^ (row & (CPR - 1))) << 4); }
+};
+
+constexpr int kLdsBytes = 65536;  // 32 KB of wave-private weight tiles + 2 x 16 KB token tile (or 16 + 2 x 16)
+
+// One workgroup pass over K for NT token tiles.  wt0 / wt1: first row of this wave's two 16-row weight
+// tiles (row stride K elements).  xsrc[q]: this lane's source row (already offset by its 16-byte piece)
+// for its q-th share of the token tile.  Accumulates acc0[j] (tile 0) and acc1[j] (tile 1).
+template <int NT, int U>
+__device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt1, int K, int ks,
+                                         const uint16_t *const (&xsrc)[NT * U / 4], unsigned char *lds,
+                                         f32x4 (&acc0)[NT], f32x4 (&acc1)[NT]) {
+  using C = Chunk<U>;
+  constexpr int IPW = NT * U / 4;  // token-tile loads per wave per chunk (4 waves share the tile)
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  unsigned char *a_lds = lds + wave * 2 * C::TILE;                 // wave-private: two weight tiles
+  unsigned char *x_lds = lds + kFfnWaves * 2 * C::TILE;            // shared: 2 buffers of NT*16 rows
+  constexpr int XBUF = NT * 16 * C::RB;
+
+  // global -> register staging
+  const int lrow = lane / C::CPR, lpc = lane % C::CPR;
+  bf16x8 GA[2][U], GX[IPW];
+  auto issue = [&](int k) {
+#pragma unroll
+    for (int q = 0; q < U; ++q) {
+      const size_t off = (size_t)(q * C::RPI + lrow) * K + k + lpc * 8;
+      GA[0][q] = ld_frag(wt0 + off);
+      GA[1][q] = ld_frag(wt1 + off);
+    }
+#pragma unroll
+    for (int q = 0; q < IPW; ++q) GX[q] = ld_frag(xsrc[q] + k);
+  };
+  auto park = [&](int buf) {
+#pragma unroll
+    for (int q = 0; q < U; ++q) {
+      const int row = q * C::RPI + lrow;
+      *reinterpret_cast<bf16x8 *>(a_lds + C::swz(row, lpc)) = GA[0][q];
+      *reinterpret_cast<bf16x8 *>(a_lds + C::TILE + C::swz(row, lpc)) = GA[1][q];
+    }
+#pragma unroll
+    for (int q = 0; q < IPW; ++q) {
+      const int g = (wave * IPW + q) * 64 + lane;
+      *reinterpret_cast<bf16x8 *>(x_lds + buf * XBUF + C::swz(g / C::CPR, g % C::CPR)) = GX[q];
+    }
+  };
+  const int r = lane & 15, kg = lane >> 4;
+  auto compute = [&](int buf) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int pc = 4 * u + kg;
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(a_lds + C::swz(r, pc));
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(a_lds + C::TILE + C::swz(r, pc));
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8 *>(x_lds + buf * XBUF + C::swz(16 * j + r, pc));
+        acc0[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0[j], 0, 0, 0);
+        acc1[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1[j], 0, 0, 0);
+      }
+    }
+  };
+
+  const int nst = K / C::KC;
+  int k = (ks / C::KC) * C::KC;
+  issue(k);
+  for (int i = 0; i < nst; ++i) {
+    park(i & 1);
+    k += C::KC;
+    k = k >= K ? k - K : k;
+    if (i + 1 < nst) issue(k);
+    __syncthreads();  // token tile i complete; also orders this wave's tile writes before its reads
+    compute(i & 1);
+  }
+  __syncthreads();  // the LDS tiles may be reused by the caller's next pass
+}
+
+template <int NT, int U>
+__device__ __forceinline__ void gateup_lds(const uint16_t *wt0, const uint16_t *wt1, const uint16_t *__restrict__ h,
+                                           const int32_t *__restrict__ perm, int M, int k, int d, int F, int beg,
+                                           int c0, int m, int f0, int ks, unsigned char *lds,
+                                           uint16_t *__restrict__ act) {
+  using C = Chunk<U>;
+  constexpr int IPW = NT * U / 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint16_t *xsrc[IPW];
+#pragma unroll
+  for (int q = 0; q < IPW; ++q) {
+    const int g = (wave * IPW + q) * 64 + lane;
+    int p = c0 + g / C::CPR;
+    p = p < m ? p : m - 1;  // pad rows repeat the last token; their columns are never stored
+    xsrc[q] = h + (size_t)(pair_index(perm, beg + p, M, k) / k) * d + (g % C::CPR) * 8;
+  }
+  f32x4 accg[NT], accu[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) accg[j] = accu[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  lds_pass<NT, U>(wt0, wt1, d, ks, xsrc, lds, accg, accu);
+  const int col = lane & 15, kg = lane >> 4;
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int p = c0 + j * 16 + col;
+    if (p < m) {
+      uint16_t o[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[i] = float_to_bf16_bits(silu_f(accg[j][i]) * accu[j][i]);
+      uint2 pk;
+      pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
+      pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
+      *reinterpret_cast<uint2 *>(act + (size_t)(beg + p) * F + f0 + 4 * kg) = pk;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
+    const uint16_t *__restrict__ h, const uint16_t *__restrict__ w_gate, const uint16_t *__restrict__ w_up,
+    const int32_t *__restrict__ seg_expert, const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm,
+    int M, int N, int k, int d, int F, uint16_t *__restrict__ act) {
+  __shared__ __align__(16) unsigned char lds[kLdsBytes];
+  const int seg = blockIdx.y;
+  const int e = seg_expert[seg];
+  const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
+  if (!segment_ok(e, beg, m, M, N, k)) return;
+  const int wave = threadIdx.x >> 6;
+  // F is a multiple of 32 but a workgroup covers 64 gate rows: the waves of a last, partial workgroup
+  // redo rows of the previous tile (same values, same destination) so that every wave reaches the barriers.
+  int f0 = (blockIdx.x * kFfnWaves + wave) * 16;
+  f0 = f0 < F ? f0 : F - 16;
+  const uint16_t *wt0 = w_gate + ((size_t)e * F + f0) * d;
+  const uint16_t *wt1 = w_up + ((size_t)e * F + f0) * d;
+  const int ks = k_stagger(blockIdx.y * gridDim.x + blockIdx.x, d);
+  for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
+    const int mc = m - c0;
+    if (mc <= 16) gateup_lds<1, 4>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
+    else if (mc <= 32) gateup_lds<2, 4>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
+    else if (mc <= 64) gateup_lds<4, 4>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
+    else gateup_lds<8, 2>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
+  }
+}
+
+template <int NT, int U>
+__device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt1, const uint16_t *__restrict__ act,
+                                         const int32_t *__restrict__ perm, int M, int k, int d, int F, int beg, int c0,
+                                         int m, int j0, int ks, unsigned char *lds, float *__restrict__ y) {
+  using C = Chunk<U>;
+  constexpr int IPW = NT * U / 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint16_t *xsrc[IPW];
+#pragma unroll
+  for (int q = 0; q < IPW; ++q) {
+    const int g = (wave * IPW + q) * 64 + lane;
+    int p = c0 + g / C::CPR;
+    p = p < m ? p : m - 1;
+    xsrc[q] = act + (size_t)(beg + p) * F + (g % C::CPR) * 8;
+  }
+  f32x4 acc0[NT], acc1[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) acc0[j] = acc1[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  lds_pass<NT, U>(wt0, wt1, F, ks, xsrc, lds, acc0, acc1);
+  const int col = lane & 15, kg = lane >> 4;
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int p = c0 + j * 16 + col;
+    if (p < m) {
+      float *dst = y + (size_t)pair_index(perm, beg + p, M, k) * d + j0 + 4 * kg;
+      *reinterpret_cast<f32x4 *>(dst) = acc0[j];
+      *reinterpret_cast<f32x4 *>(dst + 16) = acc1[j];
+    }
+  }
+}
+
+__global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
+    const uint16_t *__restrict__ act, const uint16_t *__restrict__ w_down, const int32_t *__restrict__ seg_expert,
+    const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm, int M, int N, int k, int d, int F,
+    float *__restrict__ y) {
+  __shared__ __align__(16) unsigned char lds[kLdsBytes];
+  const int seg = blockIdx.y;
+  const int e = seg_expert[seg];
+  const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
+  if (!segment_ok(e, beg, m, M, N, k)) return;
+  const int wave = threadIdx.x >> 6;
+  int j0 = (blockIdx.x * kFfnWaves + wave) * 32;
+  j0 = j0 < d ? j0 : d - 32;  // see ffn_gateup_lds_kernel
+  const uint16_t *wt0 = w_down + ((size_t)e * d + j0) * F;
+  const uint16_t *wt1 = wt0 + (size_t)16 * F;
+  const int ks = k_stagger(blockIdx.y * gridDim.x + blockIdx.x, F);
+  for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
+    const int mc = m - c0;
+    if (mc <= 16) down_lds<1, 4>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
+    else if (mc <= 32) down_lds<2, 4>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
+    else if (mc <= 64) down_lds<4, 4>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
+    else down_lds<8, 2>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
   }
 }
 
@@ -275,6 +499,22 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
   hipError_t e;
   if (ds.dtype == MOESPEC_BF16) {
     for (int pass = 1; pass <= 2; ++pass) {
+      if ((pass == 1 ? d : F) % 128 == 0) {
+        if (pass == 1) {
+          dim3 grid((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg);
+          ffn_gateup_lds_kernel<<<grid, kFfnThreads, 0, st>>>(
+              static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(wt.w_gate),
+              static_cast<const uint16_t *>(wt.w_up), seg_expert, seg_off, perm, M, ds.n_experts, k, d, F,
+              static_cast<uint16_t *>(act));
+        } else {
+          dim3 grid((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg);
+          ffn_down_lds_kernel<<<grid, kFfnThreads, 0, st>>>(static_cast<const uint16_t *>(act),
+                                                            static_cast<const uint16_t *>(wt.w_down), seg_expert,
+                                                            seg_off, perm, M, ds.n_experts, k, d, F, y);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        continue;
+      }
       switch (pick_unroll(pass == 1 ? d : F)) {
         case 4: e = launch_bf16<4>(ds, wt, h, M, n_seg, seg_expert, seg_off, perm, act, y, pass, st); break;
         case 2: e = launch_bf16<2>(ds, wt, h, M, n_seg, seg_expert, seg_off, perm, act, y, pass, st); break;
