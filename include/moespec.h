@@ -160,6 +160,7 @@ moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weight
  * shapes documented above: probs [M,N], scores [N], budget_ids [B], tok_ids [M,k], tok_w [M,k],
  * seg_expert [B], seg_off [B+1], perm [M*k], n_loaded [1].
  */
+#define MOESPEC_TRACE_POINTS 6
 typedef struct {
   double  *probs;
   double  *scores;
@@ -170,6 +171,11 @@ typedef struct {
   int32_t *seg_off;
   int32_t *perm;
   int32_t *n_loaded;
+  /* Optional timing hook for benchmarks (HOST array, or NULL): MOESPEC_TRACE_POINTS hipEvent_t handles,
+   * created by the caller with timing enabled.  They are recorded on the stream at the stage
+   * boundaries: [0] start, [1] after routing, [2] after budget + segments, [3] after the gate/up
+   * pass, [4] after the down pass, [5] after the combine. */
+  void *const *trace_events;
 } moespec_taps;
 
 moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_weights *weights,

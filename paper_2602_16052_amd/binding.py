@@ -45,7 +45,11 @@ class Weights(Structure):
 class Taps(Structure):
     _fields_ = [("probs", c_void_p), ("scores", c_void_p), ("budget_ids", c_void_p), ("tok_ids", c_void_p),
                 ("tok_w", c_void_p), ("seg_expert", c_void_p), ("seg_off", c_void_p), ("perm", c_void_p),
-                ("n_loaded", c_void_p)]
+                ("n_loaded", c_void_p), ("trace_events", POINTER(c_void_p))]
+
+
+TRACE_POINTS = 6
+TRACE_STAGES = ("route", "budget", "gate_up", "down", "combine")   # intervals between consecutive trace points
 
 
 _lib = None
@@ -223,6 +227,80 @@ def moespec_expert_ffn(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: tor
     return out
 
 
+class HipEvents:
+    """A fixed set of timing-enabled hipEvent_t handles (created through libamdhip64 directly, so that
+    their raw handles can cross the C ABI).  Used for the library's optional trace hook."""
+
+    def __init__(self, n: int):
+        self._hip = ctypes.CDLL("libamdhip64.so")
+        self._hip.hipEventCreate.argtypes = [POINTER(c_void_p)]
+        self._hip.hipEventElapsedTime.argtypes = [POINTER(ctypes.c_float), c_void_p, c_void_p]
+        self._hip.hipEventSynchronize.argtypes = [c_void_p]
+        self._hip.hipEventDestroy.argtypes = [c_void_p]
+        self._hip.hipEventRecord.argtypes = [c_void_p, c_void_p]
+        self.handles = (c_void_p * n)()
+        for i in range(n):
+            ev = c_void_p()
+            if self._hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                raise MoeSpecError(ERR_HIP, "hipEventCreate")
+            self.handles[i] = ev
+
+    def record(self, i: int, stream=None):
+        if self._hip.hipEventRecord(self.handles[i], _stream(stream)) != 0:
+            raise MoeSpecError(ERR_HIP, "hipEventRecord")
+
+    def synchronize(self, i: int):
+        if self._hip.hipEventSynchronize(self.handles[i]) != 0:
+            raise MoeSpecError(ERR_HIP, "hipEventSynchronize")
+
+    def elapsed_ms(self, i: int, j: int) -> float:
+        ms = ctypes.c_float()
+        if self._hip.hipEventElapsedTime(ctypes.byref(ms), self.handles[i], self.handles[j]) != 0:
+            raise MoeSpecError(ERR_HIP, "hipEventElapsedTime")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            for ev in self.handles:
+                if ev:
+                    self._hip.hipEventDestroy(ev)
+        except Exception:
+            pass
+
+
+class LayerForwardCall:
+    """moespec_layer_forward with its arguments marshalled once: calling the object only crosses the
+    C ABI (for tight loops, where per-call marshalling would cost more than the kernels)."""
+
+    def __init__(self, desc: LayerDesc, weights: Dict[str, torch.Tensor], h: torch.Tensor, B: int, policy: int,
+                 ws: torch.Tensor, out: torch.Tensor, ext_shortlist: Optional[torch.Tensor] = None,
+                 residual: Optional[torch.Tensor] = None, trace: Optional[HipEvents] = None,
+                 n_loaded: Optional[torch.Tensor] = None, stream=None):
+        M, dt = h.shape[0], desc.torch_dtype
+        self._keep = (weights, h, ws, out, ext_shortlist, residual, trace, n_loaded)
+        self._fn = load_library().moespec_layer_forward
+        self._cd, self._cw = desc.c(), _weights(desc, weights, True, True)
+        self._taps = None
+        if trace is not None or n_loaded is not None:
+            self._taps = Taps()
+            if trace is not None:
+                if len(trace.handles) < TRACE_POINTS:
+                    raise ValueError(f"trace needs {TRACE_POINTS} events")
+                self._taps.trace_events = ctypes.cast(trace.handles, POINTER(c_void_p))
+            if n_loaded is not None:
+                self._taps.n_loaded = _ptr(n_loaded, torch.int32, 1, "n_loaded")
+        self._args = (ctypes.byref(self._cd), ctypes.byref(self._cw), _ptr(h, dt, M * desc.d, "h"), M, int(B),
+                      int(policy), _ptr(ext_shortlist, torch.int32, max(int(B), 0), "ext_shortlist"),
+                      _ptr(residual, dt, M * desc.d, "residual"), _ptr(out, dt, M * desc.d, "out"),
+                      ctypes.byref(self._taps) if self._taps is not None else None, _ptr(ws), ws.numel(),
+                      _stream(stream))
+
+    def __call__(self):
+        st = self._fn(*self._args)
+        if st != OK:
+            raise MoeSpecError(int(st), "moespec_layer_forward")
+
+
 def moespec_layer_forward(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: torch.Tensor, B: int, policy: int,
                           ws: torch.Tensor, ext_shortlist: Optional[torch.Tensor] = None,
                           residual: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
@@ -242,7 +320,7 @@ def moespec_layer_forward(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: 
                      tok_ids=torch.empty((M, k), **i32), tok_w=torch.empty((M, k), dtype=torch.float32, device=dev),
                      seg_expert=torch.empty(nb, **i32), seg_off=torch.empty(nb + 1, **i32),
                      perm=torch.empty(M * k, **i32), n_loaded=torch.empty(1, **i32))
-        ctaps = Taps(**{key: _ptr(val) for key, val in tap_t.items()})
+        ctaps = Taps(**{key: _ptr(val) for key, val in tap_t.items()})   # trace_events stays NULL
     cd, cw = desc.c(), _weights(desc, weights, True, True)
     st = load_library().moespec_layer_forward(
         ctypes.byref(cd), ctypes.byref(cw), _ptr(h, dt, M * desc.d, "h"), M, int(B), int(policy),

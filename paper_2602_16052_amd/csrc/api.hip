@@ -135,13 +135,20 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
   int32_t *seg_expert = t.seg_expert ? t.seg_expert : w.seg_expert;
   int32_t *seg_off = t.seg_off ? t.seg_off : w.seg_off;
   int32_t *perm = t.perm ? t.perm : w.perm;
+  void *const *tr = t.trace_events;
+  auto mark = [&](int i) {
+    if (tr && tr[i]) (void)hipEventRecord(static_cast<hipEvent_t>(tr[i]), st);
+  };
+  mark(0);
   hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
+  mark(1);
   e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, t.budget_ids, tok_ids, tok_w, seg_expert,
                     seg_off, perm, t.n_loaded, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
+  mark(2);
   e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
-                        w.y, st);
+                        w.y, st, tr ? tr + 3 : nullptr);
   return from_hip(e);
 }
 

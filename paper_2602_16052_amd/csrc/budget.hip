@@ -8,6 +8,22 @@ namespace moespec {
 
 constexpr int kBudgetThreads = 256;
 
+// s_i = sum over t = 0..M-1 of probs[t, i], added strictly in ascending t; the loads of eight rows
+// are issued together so that the chain is bound by the adds, not by memory latency.
+__device__ __forceinline__ double column_sum(const double *__restrict__ probs, int M, int N, int i) {
+  double acc = 0.0;
+  int t = 0;
+  for (; t + 8 <= M; t += 8) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = probs[(size_t)(t + u) * N + i];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  for (; t < M; ++t) acc += probs[(size_t)t * N + i];
+  return acc;
+}
+
 // One workgroup per tree token.  Every workgroup recomputes the (tiny) scores and shortlist so that
 // no grid-wide synchronisation is needed; workgroup 0 also writes them out.
 __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
@@ -30,21 +46,13 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
   }
   if (ext_shortlist == nullptr) {
     // Eq. (5): s_i = sum over the M tree tokens of g_i(h_t), tokens in ascending order.
-    for (int i = tid; i < N; i += blockDim.x) {
-      double acc = 0.0;
-      for (int tt = 0; tt < M; ++tt) acc += probs[(size_t)tt * N + i];
-      s[i] = acc;
-    }
+    for (int i = tid; i < N; i += blockDim.x) s[i] = column_sum(probs, M, N, i);
     __syncthreads();
     select_topk(s, nullptr, N, B, S);
   } else {
     for (int r = tid; r < B; r += blockDim.x) S[r] = ext_shortlist[r];
     if (scores && t == 0) {
-      for (int i = tid; i < N; i += blockDim.x) {
-        double acc = 0.0;
-        for (int tt = 0; tt < M; ++tt) acc += probs[(size_t)tt * N + i];
-        s[i] = acc;
-      }
+      for (int i = tid; i < N; i += blockDim.x) s[i] = column_sum(probs, M, N, i);
     }
   }
   __syncthreads();
@@ -98,14 +106,20 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
 
 // Groups the surviving (token, slot) pairs by expert: segment i holds the pairs routed to
 // seg_expert[i], tokens ascending.  One workgroup; one wave per segment, 64 tokens per ballot.
-__global__ __launch_bounds__(kBudgetThreads) void segments_kernel(const int32_t *__restrict__ tok_ids, int M, int k,
-                                                                  int B, const int32_t *__restrict__ seg_expert,
+__global__ __launch_bounds__(kBudgetThreads) void segments_kernel(const int32_t *tok_ids, int M, int k, int B,
+                                                                  int staged, const int32_t *__restrict__ seg_expert,
                                                                   int32_t *__restrict__ seg_off,
                                                                   int32_t *__restrict__ perm,
                                                                   int32_t *__restrict__ n_loaded) {
   extern __shared__ __align__(16) unsigned char smem[];
-  int32_t *cnt = reinterpret_cast<int32_t *>(smem);  // [B] counts, then exclusive offsets
+  int32_t *cnt = reinterpret_cast<int32_t *>(smem);  // [B + 1] counts, then exclusive offsets
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwave = blockDim.x >> 6;
+  if (staged) {  // the routing table fits in LDS: read it from there instead of global memory
+    int32_t *copy = cnt + B + 1;
+    for (int i = tid; i < M * k; i += blockDim.x) copy[i] = tok_ids[i];
+    __syncthreads();
+    tok_ids = copy;
+  }
 
   for (int i = wave; i < B; i += nwave) {
     const int e = seg_expert[i];
@@ -162,8 +176,9 @@ hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int
                                                  budget_ids, seg_expert, tok_ids, tok_w);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  segments_kernel<<<1, kBudgetThreads, sizeof(int32_t) * (B + 1), st>>>(tok_ids, M, k, B, seg_expert, seg_off, perm,
-                                                                         n_loaded);
+  const int staged = (size_t)M * k <= 8192;
+  const size_t seg_smem = sizeof(int32_t) * (B + 1 + (staged ? (size_t)M * k : 0));
+  segments_kernel<<<1, kBudgetThreads, seg_smem, st>>>(tok_ids, M, k, B, staged, seg_expert, seg_off, perm, n_loaded);
   return hipGetLastError();
 }
 

@@ -134,9 +134,10 @@ hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int
                          const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
                          hipStream_t st);
+// trace (may be NULL): 3 events recorded after the gate/up pass, the down pass and the combine.
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
-                             float *y, hipStream_t st);
+                             float *y, hipStream_t st, void *const *trace = nullptr);
 
 }  // namespace moespec

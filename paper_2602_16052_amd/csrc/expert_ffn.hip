@@ -494,9 +494,12 @@ static int pick_unroll(int K) { return K % 128 == 0 ? 4 : (K % 64 == 0 ? 2 : 1);
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
-                             float *y, hipStream_t st) {
+                             float *y, hipStream_t st, void *const *trace) {
   const int d = ds.d, F = ds.d_ff, k = ds.top_k;
   hipError_t e;
+  auto mark = [&](int i) {
+    if (trace && trace[i]) (void)hipEventRecord(static_cast<hipEvent_t>(trace[i]), st);
+  };
   if (ds.dtype == MOESPEC_BF16) {
     for (int pass = 1; pass <= 2; ++pass) {
       if ((pass == 1 ? d : F) % 128 == 0) {
@@ -513,6 +516,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                                                             seg_off, perm, M, ds.n_experts, k, d, F, y);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
+        mark(pass - 1);
         continue;
       }
       switch (pick_unroll(pass == 1 ? d : F)) {
@@ -521,11 +525,14 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
         default: e = launch_bf16<1>(ds, wt, h, M, n_seg, seg_expert, seg_off, perm, act, y, pass, st); break;
       }
       if (e != hipSuccess) return e;
+      mark(pass - 1);
     }
     dim3 cgrid((d + 255) / 256, M);
     combine_kernel<uint16_t><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const uint16_t *>(residual), k, d,
                                                     static_cast<uint16_t *>(out));
-    return hipGetLastError();
+    e = hipGetLastError();
+    mark(2);
+    return e;
   }
   dim3 g1((F + kFfnWaves - 1) / kFfnWaves, n_seg);
   ffn_gateup_f32_kernel<<<g1, kFfnThreads, 0, st>>>(static_cast<const float *>(h),
@@ -533,15 +540,19 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                                                     static_cast<const float *>(wt.w_up), seg_expert, seg_off, perm, M,
                                                     ds.n_experts, k, d, F, static_cast<float *>(act));
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  mark(0);
   dim3 g2((d + kFfnWaves - 1) / kFfnWaves, n_seg);
   ffn_down_f32_kernel<<<g2, kFfnThreads, 0, st>>>(static_cast<const float *>(act),
                                                   static_cast<const float *>(wt.w_down), seg_expert, seg_off, perm, M,
                                                   ds.n_experts, k, d, F, y);
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  mark(1);
   dim3 cgrid((d + 255) / 256, M);
   combine_kernel<float><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const float *>(residual), k, d,
                                                static_cast<float *>(out));
-  return hipGetLastError();
+  e = hipGetLastError();
+  mark(2);
+  return e;
 }
 
 }  // namespace moespec

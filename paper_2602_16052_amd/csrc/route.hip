@@ -4,7 +4,7 @@
 
 namespace moespec {
 
-constexpr int kRouteThreads = 256;
+constexpr int kRouteThreads = 512;
 
 template <typename T>
 __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restrict__ h, const T *__restrict__ w_r,
@@ -13,11 +13,11 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
                                                               int32_t *__restrict__ topk_ids,
                                                               float *__restrict__ topk_w) {
   extern __shared__ __align__(16) unsigned char smem[];
-  double *g = reinterpret_cast<double *>(smem);              // [N] logits, then probabilities
-  double *red = g + N;                                       // [4] per-wave partials
-  double *wsel = red + 4;                                    // [k]
-  int32_t *sel = reinterpret_cast<int32_t *>(wsel + k);      // [k]
-  float *hrow = reinterpret_cast<float *>(sel + ((k + 1) & ~1));  // [d]
+  double *g = reinterpret_cast<double *>(smem);              // [N rounded up to even] logits, then probabilities
+  double *red = g + ((N + 1) & ~1);                                       // [8] per-wave partials
+  double *wsel = red + 8;                                    // [k]
+  int32_t *sel = reinterpret_cast<int32_t *>(wsel + ((k + 1) & ~1));      // [k]
+  float *hrow = reinterpret_cast<float *>(sel + ((k + 3) & ~3));  // [d], 16-byte aligned
 
   const int t = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwave = blockDim.x >> 6;
@@ -25,11 +25,18 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
   for (int j = tid; j < d; j += blockDim.x) hrow[j] = Elem<T>::load(h + (size_t)t * d + j);
   __syncthreads();
 
-  // logit_i = w_i . h_t (+ b_i): one wave per expert, lanes stride the hidden dimension.
+  // logit_i = w_i . h_t (+ b_i): one wave per expert, each lane takes 16-byte pieces of the row.
+  constexpr int VEC = 16 / sizeof(T);
   for (int i = wave; i < N; i += nwave) {
     const T *wi = w_r + (size_t)i * d;
     double acc = 0.0;
-    for (int j = lane; j < d; j += kWave) acc = fma((double)Elem<T>::load(wi + j), (double)hrow[j], acc);
+#pragma unroll 4
+    for (int j = lane * VEC; j < d; j += kWave * VEC) {
+      const uint4 raw = *reinterpret_cast<const uint4 *>(wi + j);
+      const T *wv = reinterpret_cast<const T *>(&raw);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc = fma((double)Elem<T>::load(wv + v), (double)hrow[j + v], acc);
+    }
     acc = wave_sum(acc);
     if (lane == 0) g[i] = acc + (b_r ? (double)b_r[i] : 0.0);
   }
@@ -76,7 +83,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
 hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *probs,
                         int32_t *topk_ids, float *topk_w, hipStream_t st) {
   const int N = ds.n_experts, k = ds.top_k, d = ds.d;
-  const size_t smem = sizeof(double) * (N + 4 + k) + sizeof(int32_t) * ((k + 1) & ~1) + sizeof(float) * d;
+  const size_t smem = sizeof(double) * (((N + 1) & ~1) + 8 + ((k + 1) & ~1)) + sizeof(int32_t) * ((k + 3) & ~3) + sizeof(float) * d;
   if (ds.dtype == MOESPEC_BF16) {
     route_kernel<uint16_t><<<M, kRouteThreads, smem, st>>>(static_cast<const uint16_t *>(h),
                                                            static_cast<const uint16_t *>(wt.w_router), wt.b_router, d,
