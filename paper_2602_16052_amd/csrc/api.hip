@@ -85,7 +85,8 @@ moespec_status moespec_route(const moespec_desc *desc, const moespec_weights *we
   if (s != MOESPEC_OK) return s;
   if ((s = check_weights(weights, true, false)) != MOESPEC_OK) return s;
   if (!h || !probs || !aligned16(h)) return MOESPEC_ERR_INVALID_ARG;
-  return from_hip(launch_route(*desc, *weights, h, M, probs, topk_ids, topk_w, static_cast<hipStream_t>(hip_stream)));
+  return from_hip(
+      launch_route(*desc, *weights, h, M, probs, topk_ids, topk_w, nullptr, static_cast<hipStream_t>(hip_stream)));
 }
 
 moespec_status moespec_budget(const moespec_desc *desc, const double *probs, int32_t M, int32_t B, int32_t policy,
@@ -96,8 +97,10 @@ moespec_status moespec_budget(const moespec_desc *desc, const double *probs, int
   if (s != MOESPEC_OK) return s;
   if ((s = check_budget(desc, B, policy)) != MOESPEC_OK) return s;
   if (!probs || !tok_ids || !tok_w || !seg_expert || !seg_off || !perm) return MOESPEC_ERR_INVALID_ARG;
+  Workspace w = carve_workspace(*desc, M, ws);
   return from_hip(launch_budget(*desc, probs, M, B, policy, ext_shortlist, scores, budget_ids, tok_ids, tok_w,
-                                seg_expert, seg_off, perm, n_loaded, static_cast<hipStream_t>(hip_stream)));
+                                seg_expert, seg_off, perm, n_loaded, w.done, false,
+                                static_cast<hipStream_t>(hip_stream)));
 }
 
 moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weights *weights, const void *h, int32_t M,
@@ -140,11 +143,11 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
     if (tr && tr[i]) (void)hipEventRecord(static_cast<hipEvent_t>(tr[i]), st);
   };
   mark(0);
-  hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, st);
+  hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, w.done, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(1);
   e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, t.budget_ids, tok_ids, tok_w, seg_expert,
-                    seg_off, perm, t.n_loaded, st);
+                    seg_off, perm, t.n_loaded, w.done, true, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(2);
   e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,

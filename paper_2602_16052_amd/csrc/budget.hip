@@ -6,129 +6,46 @@
 
 namespace moespec {
 
-constexpr int kBudgetThreads = 256;
+constexpr int kBudgetThreads = 1024;
 
-// s_i = sum over t = 0..M-1 of probs[t, i], added strictly in ascending t; the loads of eight rows
+// s_i = sum over t = 0..M-1 of probs[t, i], added strictly in ascending t; the loads of up to 32 rows
 // are issued together so that the chain is bound by the adds, not by memory latency.
 __device__ __forceinline__ double column_sum(const double *__restrict__ probs, int M, int N, int i) {
   double acc = 0.0;
-  int t = 0;
-  for (; t + 8 <= M; t += 8) {
-    double v[8];
+  for (int t = 0; t < M; t += 32) {
+    double v[32];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = probs[(size_t)(t + u) * N + i];
+    for (int u = 0; u < 32; ++u) v[u] = t + u < M ? probs[(size_t)(t + u) * N + i] : 0.0;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc += v[u];
+    for (int u = 0; u < 32; ++u) acc += v[u];  // rows past M add +0.0, which leaves the sum unchanged
   }
-  for (; t < M; ++t) acc += probs[(size_t)t * N + i];
   return acc;
 }
 
-// One workgroup per tree token.  Every workgroup recomputes the (tiny) scores and shortlist so that
-// no grid-wide synchronisation is needed; workgroup 0 also writes them out.
-__global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
-    const double *__restrict__ probs, int M, int N, int k, int B, int policy, int renorm,
-    const int32_t *__restrict__ ext_shortlist, double *__restrict__ scores, int32_t *__restrict__ budget_ids,
-    int32_t *__restrict__ seg_expert, int32_t *__restrict__ tok_ids, float *__restrict__ tok_w) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  double *s = reinterpret_cast<double *>(smem);         // [N] aggregate scores
-  double *g = s + N;                                     // [N] this token's probabilities
-  double *wsel = g + N;                                  // [k]
-  int32_t *sel = reinterpret_cast<int32_t *>(wsel + k);  // [k]
-  int32_t *S = sel + k;                                  // [B] shortlist in rank order
-  uint8_t *inS = reinterpret_cast<uint8_t *>(S + B);     // [N] membership
-
-  const int t = blockIdx.x, tid = threadIdx.x;
-
-  for (int i = tid; i < N; i += blockDim.x) {
-    g[i] = probs[(size_t)t * N + i];
-    inS[i] = 0;
-  }
-  if (ext_shortlist == nullptr) {
-    // Eq. (5): s_i = sum over the M tree tokens of g_i(h_t), tokens in ascending order.
-    for (int i = tid; i < N; i += blockDim.x) s[i] = column_sum(probs, M, N, i);
-    __syncthreads();
-    select_topk(s, nullptr, N, B, S);
-  } else {
-    for (int r = tid; r < B; r += blockDim.x) S[r] = ext_shortlist[r];
-    if (scores && t == 0) {
-      for (int i = tid; i < N; i += blockDim.x) s[i] = column_sum(probs, M, N, i);
-    }
-  }
-  __syncthreads();
-  for (int r = tid; r < B; r += blockDim.x)
-    if ((uint32_t)S[r] < (uint32_t)N) inS[S[r]] = 1;  // ids outside [0, N) in an external shortlist are ignored
-  __syncthreads();
-
-  if (t == 0) {
-    for (int i = tid; i < N; i += blockDim.x) {
-      if (scores) scores[i] = s[i];
-      if (inS[i]) {  // position of expert i among the shortlisted experts in ascending id
-        int pos = 0;
-        for (int j = 0; j < i; ++j) pos += inS[j];
-        seg_expert[pos] = i;
-      }
-    }
-    int n_member = 0;  // < B only if an external shortlist repeats or misnames an expert
-    for (int j = 0; j < N; ++j) n_member += inS[j];
-    for (int r = tid; r < B; r += blockDim.x) {
-      if (r >= n_member) seg_expert[r] = -1;
-      if (budget_ids) budget_ids[r] = S[r];
-    }
-  }
-
-  if (policy == MOESPEC_TRUNCATE) {
-    // Natural top-k and its weights, then drop the slots outside S; kept weights are unchanged.
-    select_topk(g, nullptr, N, k, sel);
-    __syncthreads();
-    mixing_weights(g, sel, k, renorm, wsel);
-    __syncthreads();
-    for (int j = tid; j < k; j += blockDim.x) {
-      const bool keep = inS[sel[j]] != 0;
-      tok_ids[(size_t)t * k + j] = keep ? sel[j] : -1;
-      tok_w[(size_t)t * k + j] = keep ? (float)wsel[j] : 0.0f;
-    }
-  } else {
-    // Top-k inside S by g_i(h_t); weights over the constrained selection.  Slots stay unfilled (-1)
-    // only when an external shortlist names fewer than k valid experts.
-    for (int j = tid; j < k; j += blockDim.x) sel[j] = -1;
-    __syncthreads();
-    select_topk(g, inS, N, k, sel);
-    __syncthreads();
-    mixing_weights(g, sel, k, renorm, wsel);
-    __syncthreads();
-    for (int j = tid; j < k; j += blockDim.x) {
-      tok_ids[(size_t)t * k + j] = sel[j];
-      tok_w[(size_t)t * k + j] = (float)wsel[j];
-    }
-  }
-}
-
 // Groups the surviving (token, slot) pairs by expert: segment i holds the pairs routed to
-// seg_expert[i], tokens ascending.  One workgroup; one wave per segment, 64 tokens per ballot.
-__global__ __launch_bounds__(kBudgetThreads) void segments_kernel(const int32_t *tok_ids, int M, int k, int B,
-                                                                  int staged, const int32_t *__restrict__ seg_expert,
-                                                                  int32_t *__restrict__ seg_off,
-                                                                  int32_t *__restrict__ perm,
-                                                                  int32_t *__restrict__ n_loaded) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  int32_t *cnt = reinterpret_cast<int32_t *>(smem);  // [B + 1] counts, then exclusive offsets
+// seg_expert[i], tokens ascending.  Run by one whole workgroup; one wave per segment at a time,
+// 64 tokens per ballot.  The routing table is staged in LDS slot-major (lanes read consecutive
+// words) when it fits.  lds: (2 B + 1 + (staged ? M k : 0)) int32.
+__device__ void build_segments(const int32_t *tok_ids, int M, int k, int B, int staged, const int32_t *seg_expert,
+                               int32_t *seg_off, int32_t *perm, int32_t *n_loaded, int32_t *lds) {
+  int32_t *cnt = lds;           // [B + 1] counts, then exclusive offsets
+  int32_t *sexp = cnt + B + 1;  // [B] seg_expert
+  int32_t *copy = sexp + B;     // [k][M] routing table, slot-major (if staged)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwave = blockDim.x >> 6;
-  if (staged) {  // the routing table fits in LDS: read it from there instead of global memory
-    int32_t *copy = cnt + B + 1;
-    for (int i = tid; i < M * k; i += blockDim.x) copy[i] = tok_ids[i];
-    __syncthreads();
-    tok_ids = copy;
-  }
+  for (int i = tid; i < B; i += blockDim.x) sexp[i] = seg_expert[i];
+  if (staged)
+    for (int i = tid; i < M * k; i += blockDim.x) copy[(i % k) * M + i / k] = tok_ids[i];
+  __syncthreads();
+  auto id_at = [&](int t, int j) { return staged ? copy[j * M + t] : tok_ids[(size_t)t * k + j]; };
 
   for (int i = wave; i < B; i += nwave) {
-    const int e = seg_expert[i];
+    const int e = sexp[i];
     int c = 0;
     for (int t0 = 0; e >= 0 && t0 < M; t0 += kWave) {
       const int t = t0 + lane;
       bool has = false;
       if (t < M)
-        for (int j = 0; j < k; ++j) has |= (tok_ids[(size_t)t * k + j] == e);
+        for (int j = 0; j < k; ++j) has |= (id_at(t, j) == e);
       c += __popcll(__ballot(has));
     }
     if (lane == 0) cnt[i] = c;
@@ -151,14 +68,14 @@ __global__ __launch_bounds__(kBudgetThreads) void segments_kernel(const int32_t 
   const int P = cnt[B];
   for (int p = P + tid; p < M * k; p += blockDim.x) perm[p] = -1;
   for (int i = wave; i < B; i += nwave) {
-    const int e = seg_expert[i];
+    const int e = sexp[i];
     int base = cnt[i];
     for (int t0 = 0; e >= 0 && t0 < M; t0 += kWave) {
       const int t = t0 + lane;
       int slot = -1;
       if (t < M)
         for (int j = 0; j < k; ++j)
-          if (tok_ids[(size_t)t * k + j] == e) slot = j;
+          if (id_at(t, j) == e) slot = j;
       const unsigned long long mask = __ballot(slot >= 0);
       if (slot >= 0) perm[base + __popcll(mask & ((1ull << lane) - 1ull))] = t * k + slot;
       base += __popcll(mask);
@@ -166,19 +83,127 @@ __global__ __launch_bounds__(kBudgetThreads) void segments_kernel(const int32_t 
   }
 }
 
+// One workgroup per tree token.  Every workgroup recomputes the (tiny) scores and shortlist so that
+// no grid-wide synchronisation is needed; workgroup 0 also writes them out.  The workgroup that
+// finishes last (ticket counter `done`, zero at launch) builds the segments from everybody's rows.
+__global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
+    const double *__restrict__ probs, int M, int N, int k, int B, int policy, int renorm,
+    const int32_t *__restrict__ ext_shortlist, double *__restrict__ scores, int32_t *__restrict__ budget_ids,
+    int32_t *__restrict__ seg_expert, int32_t *tok_ids, float *__restrict__ tok_w, int32_t *__restrict__ seg_off,
+    int32_t *__restrict__ perm, int32_t *__restrict__ n_loaded, int staged, int32_t *done) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  double *s = reinterpret_cast<double *>(smem);                  // [N] aggregate scores
+  double *g = s + N;                                              // [N] this token's probabilities
+  double *wsel = g + N;                                           // [k, even] + denominator
+  int32_t *sel = reinterpret_cast<int32_t *>(wsel + ((k + 1) & ~1) + 2);  // [k]
+  int32_t *S = sel + k;                                           // [B] shortlist in rank order
+  int32_t *rank = S + B;                                          // [N] scratch of the selections
+  int32_t *flag = rank + N;                                       // [1] "this workgroup is the last one"
+  uint8_t *inS = reinterpret_cast<uint8_t *>(flag + 1);           // [N] membership
+
+  const int t = blockIdx.x, tid = threadIdx.x;
+
+  for (int i = tid; i < N; i += blockDim.x) {
+    g[i] = probs[(size_t)t * N + i];
+    inS[i] = 0;
+  }
+  if (ext_shortlist == nullptr) {
+    // Eq. (5): s_i = sum over the M tree tokens of g_i(h_t), tokens in ascending order.
+    for (int i = tid; i < N; i += blockDim.x) s[i] = column_sum(probs, M, N, i);
+    __syncthreads();
+    select_topk(s, nullptr, N, B, S, rank);
+  } else {
+    for (int r = tid; r < B; r += blockDim.x) S[r] = ext_shortlist[r];
+    if (scores && t == 0)
+      for (int i = tid; i < N; i += blockDim.x) s[i] = column_sum(probs, M, N, i);
+  }
+  __syncthreads();
+  for (int r = tid; r < B; r += blockDim.x)
+    if ((uint32_t)S[r] < (uint32_t)N) inS[S[r]] = 1;  // ids outside [0, N) in an external shortlist are ignored
+  __syncthreads();
+
+  if (t == 0) {
+    for (int i = tid; i < N; i += blockDim.x) {
+      if (scores) scores[i] = s[i];
+      if (inS[i]) {  // position of expert i among the shortlisted experts in ascending id
+        int pos = 0;
+        for (int j = 0; j < i; ++j) pos += inS[j];
+        seg_expert[pos] = i;
+      }
+    }
+    if (tid < B) {
+      int n_member = 0;  // < B only if an external shortlist repeats or misnames an expert
+      for (int j = 0; j < N; ++j) n_member += inS[j];
+      for (int r = tid; r < B; r += blockDim.x) {
+        if (r >= n_member) seg_expert[r] = -1;
+        if (budget_ids) budget_ids[r] = S[r];
+      }
+    }
+  }
+
+  if (policy == MOESPEC_TRUNCATE) {
+    // Natural top-k and its weights, then drop the slots outside S; kept weights are unchanged.
+    select_topk(g, nullptr, N, k, sel, rank);
+    __syncthreads();
+    mixing_weights(g, sel, k, renorm, wsel, wsel + ((k + 1) & ~1));
+    __syncthreads();
+    for (int j = tid; j < k; j += blockDim.x) {
+      const bool keep = inS[sel[j]] != 0;
+      tok_ids[(size_t)t * k + j] = keep ? sel[j] : -1;
+      tok_w[(size_t)t * k + j] = keep ? (float)wsel[j] : 0.0f;
+    }
+  } else {
+    // Top-k inside S by g_i(h_t); weights over the constrained selection.  Slots stay unfilled (-1)
+    // only when an external shortlist names fewer than k valid experts.
+    for (int j = tid; j < k; j += blockDim.x) sel[j] = -1;
+    __syncthreads();
+    select_topk(g, inS, N, k, sel, rank);
+    __syncthreads();
+    mixing_weights(g, sel, k, renorm, wsel, wsel + ((k + 1) & ~1));
+    __syncthreads();
+    for (int j = tid; j < k; j += blockDim.x) {
+      tok_ids[(size_t)t * k + j] = sel[j];
+      tok_w[(size_t)t * k + j] = (float)wsel[j];
+    }
+  }
+
+  // Last workgroup to arrive groups the pairs of all tokens.  One thread publishes the workgroup's
+  // rows (the barrier before it orders everybody's stores first) and takes the ticket; device-scope
+  // fences are expensive, so they are not executed by every wave.
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    const bool is_last = atomicAdd(done, 1) == (int)gridDim.x - 1;
+    if (is_last) __threadfence();
+    *flag = is_last;
+  }
+  __syncthreads();
+  const bool last = *flag != 0;
+  __syncthreads();  // everybody has read the flag before the LDS is reused below
+  if (!last) return;
+  build_segments(tok_ids, M, k, B, staged, seg_expert, seg_off, perm, n_loaded, reinterpret_cast<int32_t *>(smem));
+}
+
+__global__ void zero_words_kernel(int32_t *p, int n) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
+}
+
 hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
                          const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
-                         hipStream_t st) {
+                         int32_t *done, bool done_is_zero, hipStream_t st) {
   const int N = ds.n_experts, k = ds.top_k;
-  const size_t smem = sizeof(double) * (2 * N + k) + sizeof(int32_t) * (k + B) + N;
-  budget_kernel<<<M, kBudgetThreads, smem, st>>>(probs, M, N, k, B, policy, ds.renorm, ext_shortlist, scores,
-                                                 budget_ids, seg_expert, tok_ids, tok_w);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (!done_is_zero) {
+    zero_words_kernel<<<1, 64, 0, st>>>(done, 1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   const int staged = (size_t)M * k <= 8192;
-  const size_t seg_smem = sizeof(int32_t) * (B + 1 + (staged ? (size_t)M * k : 0));
-  segments_kernel<<<1, kBudgetThreads, seg_smem, st>>>(tok_ids, M, k, B, staged, seg_expert, seg_off, perm, n_loaded);
+  const size_t smem_sel = sizeof(double) * (2 * N + ((k + 1) & ~1) + 2) + sizeof(int32_t) * (k + B + N + 1) + N;
+  const size_t smem_seg = sizeof(int32_t) * (2 * B + 1 + (staged ? (size_t)M * k : 0));
+  budget_kernel<<<M, kBudgetThreads, smem_sel > smem_seg ? smem_sel : smem_seg, st>>>(
+      probs, M, N, k, B, policy, ds.renorm, ext_shortlist, scores, budget_ids, seg_expert, tok_ids, tok_w, seg_off, perm,
+      n_loaded, staged, done);
   return hipGetLastError();
 }
 

@@ -58,29 +58,53 @@ __device__ __forceinline__ double wave_max(double v) {
 
 // Rank-count selection of the k best of v[0..n) restricted to candidates with member[i] != 0
 // (member == nullptr: all).  sel[r] receives the index with rank r < k.  Equivalent to sorting by
-// (value descending, index ascending) and keeping the first k.
-__device__ inline void select_topk(const double *v, const uint8_t *member, int n, int k, int32_t *sel) {
-  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+// (value descending, index ascending) and keeping the first k.  v, member, sel and the scratch
+// rank[n] live in LDS.  Called by every thread of the workgroup (it synchronises); the caller
+// synchronises again before reading sel.  The n x n comparisons are spread over the whole workgroup:
+// thread (i, part) counts the rivals of candidate i inside its part of the index range and adds its
+// count to rank[i] with an integer LDS atomic (order-independent, hence deterministic).
+__device__ inline void select_topk(const double *v, const uint8_t *member, int n, int k, int32_t *sel, int32_t *rank) {
+  const int nt = blockDim.x, tid = threadIdx.x;
+  int np2 = 1;
+  while (np2 < n) np2 <<= 1;
+  for (int x = tid; x < n; x += nt) rank[x] = 0;
+  __syncthreads();
+  const int parts = np2 <= nt ? nt / np2 : 1;
+  const int chunk = (n + parts - 1) / parts;
+  for (int i = np2 <= nt ? (tid & (np2 - 1)) : tid; i < n; i += np2 <= nt ? n : nt) {
+    const int part = np2 <= nt ? tid / np2 : 0;
     if (member && !member[i]) continue;
+    const int j0 = part * chunk, j1 = min(n, j0 + chunk);
     const double vi = v[i];
-    int rank = 0;
-    for (int j = 0; j < n; ++j) {
-      if (member && !member[j]) continue;
-      rank += ranks_before(v[j], j, vi, i) ? 1 : 0;
+    int cnt = 0;
+    if (member) {
+#pragma unroll 4
+      for (int j = j0; j < j1; ++j) cnt += (member[j] && ranks_before(v[j], j, vi, i)) ? 1 : 0;
+    } else {
+#pragma unroll 4
+      for (int j = j0; j < j1; ++j) cnt += ranks_before(v[j], j, vi, i) ? 1 : 0;
     }
-    if (rank < k) sel[rank] = i;
+    if (cnt) atomicAdd(&rank[i], cnt);
   }
+  __syncthreads();
+  for (int x = tid; x < n; x += nt)
+    if ((!member || member[x]) && rank[x] < k) sel[rank[x]] = x;
 }
 
 // Mixing weights of the slots sel[0..k): raw g or g / sum over the slots (summed in slot order).
-// An unfilled slot (sel < 0) gets weight 0.
-__device__ inline void mixing_weights(const double *g, const int32_t *sel, int k, int renorm, double *w) {
-  if (threadIdx.x == 0) {
-    double denom = 0.0;
+// An unfilled slot (sel < 0) gets weight 0.  Called by every thread (it synchronises); denom is one
+// LDS double of scratch.
+__device__ inline void mixing_weights(const double *g, const int32_t *sel, int k, int renorm, double *w,
+                                      double *denom) {
+  if (threadIdx.x == 0 && renorm) {
+    double acc = 0.0;
     for (int s = 0; s < k; ++s)
-      if (sel[s] >= 0) denom += g[sel[s]];
-    for (int s = 0; s < k; ++s) w[s] = sel[s] < 0 ? 0.0 : (renorm ? g[sel[s]] / denom : g[sel[s]]);
+      if (sel[s] >= 0) acc += g[sel[s]];
+    *denom = acc;
   }
+  __syncthreads();
+  for (int s = threadIdx.x; s < k; s += blockDim.x)
+    w[s] = sel[s] < 0 ? 0.0 : (renorm ? g[sel[s]] / *denom : g[sel[s]]);
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -96,6 +120,7 @@ struct Workspace {
   int32_t *seg_off;   // [N + 1]
   int32_t *perm;      // [M * k]
   int32_t *n_loaded;  // [1]
+  int32_t *done;      // [1] ticket counter of the budget stage
   void *act;          // [M * k, F] dtype
   float *y;           // [M * k, d]
   size_t bytes;
@@ -121,6 +146,7 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
   w.seg_off = static_cast<int32_t *>(take(sizeof(int32_t) * (N + 1)));
   w.perm = static_cast<int32_t *>(take(sizeof(int32_t) * M * k));
   w.n_loaded = static_cast<int32_t *>(take(sizeof(int32_t)));
+  w.done = static_cast<int32_t *>(take(sizeof(int32_t)));
   w.act = take(es * M * k * F);
   w.y = static_cast<float *>(take(sizeof(float) * M * k * d));
   w.bytes = off;
@@ -128,12 +154,13 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
 }
 
 // Launchers (defined in the .hip files).  Each returns hipGetLastError() after its launches.
+// zero_word (may be NULL): one int32 that the kernel sets to 0 (the ticket counter of the budget stage).
 hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *probs,
-                        int32_t *topk_ids, float *topk_w, hipStream_t st);
+                        int32_t *topk_ids, float *topk_w, int32_t *zero_word, hipStream_t st);
 hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
                          const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
-                         hipStream_t st);
+                         int32_t *done, bool done_is_zero, hipStream_t st);
 // trace (may be NULL): 3 events recorded after the gate/up pass, the down pass and the combine.
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,

@@ -455,18 +455,47 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_down_f32_kernel(
 }
 
 // ---- combine: out[t] = residual[t] + sum over surviving slots (slot order) of w * y[t*k+slot] ---
+// Four consecutive outputs per thread.  The rows of dropped slots hold stale scratch: they are loaded
+// (valid memory) but never enter the sum.
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ y, const int32_t *__restrict__ tok_ids,
                                                       const float *__restrict__ tok_w, const T *__restrict__ residual,
                                                       int k, int d, T *__restrict__ out) {
   const int t = blockIdx.y;
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (j >= d) return;
-  float acc = residual ? Elem<T>::load(residual + (size_t)t * d + j) : 0.0f;
-  for (int s = 0; s < k; ++s) {
-    if (tok_ids[(size_t)t * k + s] >= 0) acc = fmaf(tok_w[(size_t)t * k + s], y[((size_t)t * k + s) * d + j], acc);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (residual) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = Elem<T>::load(residual + (size_t)t * d + j + i);
   }
-  Elem<T>::store(out + (size_t)t * d + j, acc);
+  const float *yt = y + (size_t)t * k * d + j;
+  const int32_t *ids = tok_ids + (size_t)t * k;
+  const float *wt = tok_w + (size_t)t * k;
+  int s = 0;
+  for (; s + 4 <= k; s += 4) {
+    f32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const f32x4 *>(yt + (size_t)(s + u) * d);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (ids[s + u] >= 0) {
+        const float w = wt[s + u];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = fmaf(w, v[u][i], acc[i]);
+      }
+    }
+  }
+  for (; s < k; ++s) {
+    if (ids[s] >= 0) {
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(yt + (size_t)s * d);
+      const float w = wt[s];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = fmaf(w, v[i], acc[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) Elem<T>::store(out + (size_t)t * d + j + i, acc[i]);
 }
 
 template <int U>
@@ -527,7 +556,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
       if (e != hipSuccess) return e;
       mark(pass - 1);
     }
-    dim3 cgrid((d + 255) / 256, M);
+    dim3 cgrid((d / 4 + 255) / 256, M);
     combine_kernel<uint16_t><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const uint16_t *>(residual), k, d,
                                                     static_cast<uint16_t *>(out));
     e = hipGetLastError();
@@ -547,7 +576,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                                                   ds.n_experts, k, d, F, y);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   mark(1);
-  dim3 cgrid((d + 255) / 256, M);
+  dim3 cgrid((d / 4 + 255) / 256, M);
   combine_kernel<float><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const float *>(residual), k, d,
                                                static_cast<float *>(out));
   e = hipGetLastError();

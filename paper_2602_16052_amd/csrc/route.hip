@@ -1,67 +1,109 @@
 // Stage 1 of Algorithm 1: router projection, softmax over all N experts (Eq. (1)), per-token
-// top-k and mixing weights (Section 2.1).  One workgroup per tree token; every decision in fp64.
+// top-k and mixing weights (Section 2.1).  Every decision in fp64.
+//
+// Two kernels.  The projection is spread over (token, group of 4 experts) workgroups so that the
+// whole chip takes part: converting bf16 operands to fp64 costs several vector instructions per
+// element, and one workgroup per token would leave that work on M compute units.  The softmax and
+// the top-k then need one small workgroup per token.  Cross-lane fp64 shuffles are slow on this
+// hardware (two 32-bit permutes per step), so all reductions go through LDS.
 #include "common.h"
 
 namespace moespec {
 
-constexpr int kRouteThreads = 512;
+constexpr int kLogitThreads = 256;
+constexpr int kRowsPerGroup = 4;                               // router rows per workgroup
+constexpr int kSlices = kLogitThreads / kRowsPerGroup;         // threads that share one row (= 64)
+constexpr int kSoftmaxThreads = 256;
 
+// logits[t, i] = w_i . h_t (+ b_i).  Thread (el, sl) takes the 16-byte pieces sl, sl+64, ... of row
+// i = 4 blockIdx.x + el and of h_t; all loads of a batch are issued together (the router weights of a
+// layer are cold in every cache).
 template <typename T>
-__global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restrict__ h, const T *__restrict__ w_r,
-                                                              const float *__restrict__ b_r, int d, int N, int k,
-                                                              int renorm, double *__restrict__ probs,
-                                                              int32_t *__restrict__ topk_ids,
-                                                              float *__restrict__ topk_w) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  double *g = reinterpret_cast<double *>(smem);              // [N rounded up to even] logits, then probabilities
-  double *red = g + ((N + 1) & ~1);                                       // [8] per-wave partials
-  double *wsel = red + 8;                                    // [k]
-  int32_t *sel = reinterpret_cast<int32_t *>(wsel + ((k + 1) & ~1));      // [k]
-  float *hrow = reinterpret_cast<float *>(sel + ((k + 3) & ~3));  // [d], 16-byte aligned
-
-  const int t = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwave = blockDim.x >> 6;
-
-  for (int j = tid; j < d; j += blockDim.x) hrow[j] = Elem<T>::load(h + (size_t)t * d + j);
-  __syncthreads();
-
-  // logit_i = w_i . h_t (+ b_i): one wave per expert, each lane takes 16-byte pieces of the row.
-  constexpr int VEC = 16 / sizeof(T);
-  for (int i = wave; i < N; i += nwave) {
-    const T *wi = w_r + (size_t)i * d;
-    double acc = 0.0;
-#pragma unroll 4
-    for (int j = lane * VEC; j < d; j += kWave * VEC) {
-      const uint4 raw = *reinterpret_cast<const uint4 *>(wi + j);
-      const T *wv = reinterpret_cast<const T *>(&raw);
+__global__ __launch_bounds__(kLogitThreads) void logits_kernel(const T *__restrict__ h, const T *__restrict__ w_r,
+                                                               const float *__restrict__ b_r, int d, int N,
+                                                               double *__restrict__ logits) {
+  __shared__ double part[kLogitThreads];
+  __shared__ double part2[kRowsPerGroup * 8];
+  const int t = blockIdx.y, tid = threadIdx.x;
+  const int el = tid / kSlices, sl = tid % kSlices;
+  const int e = blockIdx.x * kRowsPerGroup + el;
+  constexpr int VEC = 16 / sizeof(T);  // elements per 16-byte piece
+  constexpr int PB = 4;                // pieces in flight per operand
+  const int npieces = d / VEC;         // d is a multiple of VEC
+  const T *wrow = w_r + (size_t)(e < N ? e : N - 1) * d;
+  const T *hrow = h + (size_t)t * d;
+  double acc = 0.0;
+  for (int p0 = 0; p0 < npieces; p0 += PB * kSlices) {
+    uint4 wr[PB], hr[PB];
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) acc = fma((double)Elem<T>::load(wv + v), (double)hrow[j + v], acc);
+    for (int q = 0; q < PB; ++q) {
+      const int pc = p0 + sl + q * kSlices;
+      const bool ok = pc < npieces;
+      wr[q] = ok ? *reinterpret_cast<const uint4 *>(wrow + (size_t)pc * VEC) : uint4{0u, 0u, 0u, 0u};
+      hr[q] = ok ? *reinterpret_cast<const uint4 *>(hrow + (size_t)pc * VEC) : uint4{0u, 0u, 0u, 0u};
     }
-    acc = wave_sum(acc);
-    if (lane == 0) g[i] = acc + (b_r ? (double)b_r[i] : 0.0);
+#pragma unroll
+    for (int q = 0; q < PB; ++q)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v)
+        acc = fma((double)Elem<T>::load(reinterpret_cast<const T *>(&wr[q]) + v),
+                  (double)Elem<T>::load(reinterpret_cast<const T *>(&hr[q]) + v), acc);
+  }
+  part[tid] = acc;
+  __syncthreads();
+  if (sl < 8) {
+    double a = 0.0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) a += part[el * kSlices + sl * 8 + q];
+    part2[el * 8 + sl] = a;
   }
   __syncthreads();
+  if (sl == 0 && e < N) {
+    double a = 0.0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) a += part2[el * 8 + q];
+    logits[(size_t)t * N + e] = a + (b_r ? (double)b_r[e] : 0.0);
+  }
+}
 
-  // softmax, max-subtracted
-  double m = -INFINITY;
-  for (int i = tid; i < N; i += blockDim.x) m = fmax(m, g[i]);
-  m = wave_max(m);
-  if (lane == 0) red[wave] = m;
+// probs[t, :] = softmax(logits[t, :]) in place (max-subtracted), then the natural top-k and its mixing
+// weights if asked for.  One workgroup per token.
+__global__ __launch_bounds__(kSoftmaxThreads) void softmax_topk_kernel(double *__restrict__ probs, int N, int k,
+                                                                       int renorm, int32_t *__restrict__ topk_ids,
+                                                                       float *__restrict__ topk_w,
+                                                                       int32_t *__restrict__ zero_word) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  double *g = reinterpret_cast<double *>(smem);               // [N, even] logits, then probabilities
+  double *part = g + ((N + 1) & ~1);                          // [32] partial reductions
+  double *wsel = part + 32;                                   // [k, even] + 1 denominator (+1 pad)
+  int32_t *sel = reinterpret_cast<int32_t *>(wsel + ((k + 1) & ~1) + 2);  // [k, multiple of 4]
+  int32_t *rank = sel + ((k + 3) & ~3);                       // [N]
+  const int t = blockIdx.x, tid = threadIdx.x;
+  if (zero_word && t == 0 && tid == 0) *zero_word = 0;
+  for (int i = tid; i < N; i += blockDim.x) g[i] = probs[(size_t)t * N + i];
   __syncthreads();
-  m = red[0];
-  for (int w = 1; w < nwave; ++w) m = fmax(m, red[w]);
-  __syncthreads();
-  double part = 0.0;
-  for (int i = tid; i < N; i += blockDim.x) {
-    const double e = exp(g[i] - m);
-    g[i] = e;
-    part += e;
+  // 32 strided partial results, then every thread folds the 32 in index order
+  if (tid < 32) {
+    double m = -INFINITY;
+    for (int i = tid; i < N; i += 32) m = fmax(m, g[i]);
+    part[tid] = m;
   }
-  part = wave_sum(part);
-  if (lane == 0) red[wave] = part;
   __syncthreads();
-  double denom = red[0];
-  for (int w = 1; w < nwave; ++w) denom += red[w];
+  double m = part[0];
+#pragma unroll
+  for (int j = 1; j < 32; ++j) m = fmax(m, part[j]);
+  __syncthreads();
+  for (int i = tid; i < N; i += blockDim.x) g[i] = exp(g[i] - m);
+  __syncthreads();
+  if (tid < 32) {
+    double a = 0.0;
+    for (int i = tid; i < N; i += 32) a += g[i];
+    part[tid] = a;
+  }
+  __syncthreads();
+  double denom = part[0];
+#pragma unroll
+  for (int j = 1; j < 32; ++j) denom += part[j];
   for (int i = tid; i < N; i += blockDim.x) {
     const double p = g[i] / denom;
     g[i] = p;
@@ -70,9 +112,9 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
   __syncthreads();
 
   if (topk_ids == nullptr && topk_w == nullptr) return;
-  select_topk(g, nullptr, N, k, sel);
+  select_topk(g, nullptr, N, k, sel, rank);
   __syncthreads();
-  mixing_weights(g, sel, k, renorm, wsel);
+  mixing_weights(g, sel, k, renorm, wsel, wsel + ((k + 1) & ~1));
   __syncthreads();
   for (int s = tid; s < k; s += blockDim.x) {
     if (topk_ids) topk_ids[(size_t)t * k + s] = sel[s];
@@ -81,18 +123,23 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *__restric
 }
 
 hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *probs,
-                        int32_t *topk_ids, float *topk_w, hipStream_t st) {
+                        int32_t *topk_ids, float *topk_w, int32_t *zero_word, hipStream_t st) {
   const int N = ds.n_experts, k = ds.top_k, d = ds.d;
-  const size_t smem = sizeof(double) * (((N + 1) & ~1) + 8 + ((k + 1) & ~1)) + sizeof(int32_t) * ((k + 3) & ~3) + sizeof(float) * d;
+  dim3 grid((N + kRowsPerGroup - 1) / kRowsPerGroup, M);
   if (ds.dtype == MOESPEC_BF16) {
-    route_kernel<uint16_t><<<M, kRouteThreads, smem, st>>>(static_cast<const uint16_t *>(h),
-                                                           static_cast<const uint16_t *>(wt.w_router), wt.b_router, d,
-                                                           N, k, ds.renorm, probs, topk_ids, topk_w);
+    logits_kernel<uint16_t><<<grid, kLogitThreads, 0, st>>>(static_cast<const uint16_t *>(h),
+                                                            static_cast<const uint16_t *>(wt.w_router), wt.b_router, d,
+                                                            N, probs);
   } else {
-    route_kernel<float><<<M, kRouteThreads, smem, st>>>(static_cast<const float *>(h),
-                                                        static_cast<const float *>(wt.w_router), wt.b_router, d, N, k,
-                                                        ds.renorm, probs, topk_ids, topk_w);
+    logits_kernel<float><<<grid, kLogitThreads, 0, st>>>(static_cast<const float *>(h),
+                                                         static_cast<const float *>(wt.w_router), wt.b_router, d, N,
+                                                         probs);
   }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t smem = sizeof(double) * (((N + 1) & ~1) + 32 + ((k + 1) & ~1) + 2) +
+                      sizeof(int32_t) * (((k + 3) & ~3) + N);
+  softmax_topk_kernel<<<M, kSoftmaxThreads, smem, st>>>(probs, N, k, ds.renorm, topk_ids, topk_w, zero_word);
   return hipGetLastError();
 }
 
