@@ -37,6 +37,11 @@ __device__ __forceinline__ int pair_index(const int32_t *perm, int pos, int M, i
 }
 
 __device__ __forceinline__ bf16x8 ld_frag(const uint16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
+// Weight bytes are read exactly once: load them with the non-temporal hint so that the stream does
+// not push the (re-read) token rows out of the caches.
+__device__ __forceinline__ bf16x8 ld_stream(const uint16_t *p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const bf16x8 *>(p));
+}
 
 // acc0[j] += A0 . B_j, acc1[j] += A1 . B_j over K, for NT token tiles; U K-steps of 32 per stage,
 // two register stages so that the next stage's loads are in flight during the current MFMAs.
@@ -239,8 +244,8 @@ __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt
 #pragma unroll
     for (int q = 0; q < U; ++q) {
       const size_t off = (size_t)(q * C::RPI + lrow) * K + k + lpc * 8;
-      GA[0][q] = ld_frag(wt0 + off);
-      GA[1][q] = ld_frag(wt1 + off);
+      GA[0][q] = ld_stream(wt0 + off);
+      GA[1][q] = ld_stream(wt1 + off);
     }
 #pragma unroll
     for (int q = 0; q < IPW; ++q) GX[q] = ld_frag(xsrc[q] + k);
