@@ -89,6 +89,19 @@ __device__ __forceinline__ void stream_rows(const uint16_t *a0, const uint16_t *
   }
 }
 
+// Workgroup -> (segment, row tile) for the LDS-tiled passes.  Workgroups are handed to the 8 XCDs
+// round-robin by linear id, and each XCD has an L2 of its own: all row tiles of one segment are given
+// ids that are equal modulo 8, so that a segment's token rows are fetched into one L2 and then hit
+// there by the other workgroups of the segment (which start together and walk K in the same order).
+constexpr int kXcds = 8;
+__device__ __forceinline__ void xcd_item(int tiles, int n_seg, int &seg, int &tile) {
+  const int bid = blockIdx.x, slot = bid / kXcds;
+  seg = bid % kXcds + kXcds * (slot / tiles);
+  tile = slot % tiles;
+  if (seg >= n_seg) seg = -1;
+}
+inline int xcd_grid(int tiles, int n_seg) { return kXcds * tiles * ((n_seg + kXcds - 1) / kXcds); }
+
 // Start offset (elements) of a wave's walk over K: 128 elements (256 bytes) apart for consecutive waves.
 __device__ __forceinline__ int k_stagger(int wave_id, int K) { return (int)(((long long)wave_id * 128) % K); }
 
@@ -332,20 +345,22 @@ __device__ __forceinline__ void gateup_lds(const uint16_t *wt0, const uint16_t *
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
     const uint16_t *__restrict__ h, const uint16_t *__restrict__ w_gate, const uint16_t *__restrict__ w_up,
     const int32_t *__restrict__ seg_expert, const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm,
-    int M, int N, int k, int d, int F, uint16_t *__restrict__ act) {
+    int n_seg, int M, int N, int k, int d, int F, uint16_t *__restrict__ act) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
-  const int seg = blockIdx.y;
+  int seg, tile;
+  xcd_item((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg, seg, tile);
+  if (seg < 0) return;
   const int e = seg_expert[seg];
   const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
   if (!segment_ok(e, beg, m, M, N, k)) return;
   const int wave = threadIdx.x >> 6;
   // F is a multiple of 32 but a workgroup covers 64 gate rows: the waves of a last, partial workgroup
   // redo rows of the previous tile (same values, same destination) so that every wave reaches the barriers.
-  int f0 = (blockIdx.x * kFfnWaves + wave) * 16;
+  int f0 = (tile * kFfnWaves + wave) * 16;
   f0 = f0 < F ? f0 : F - 16;
   const uint16_t *wt0 = w_gate + ((size_t)e * F + f0) * d;
   const uint16_t *wt1 = w_up + ((size_t)e * F + f0) * d;
-  const int ks = k_stagger(blockIdx.y * gridDim.x + blockIdx.x, d);
+  const int ks = k_stagger(seg, d);
   for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
     const int mc = m - c0;
     if (mc <= 16) gateup_lds<1, 4>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
@@ -388,19 +403,21 @@ __device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt
 
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
     const uint16_t *__restrict__ act, const uint16_t *__restrict__ w_down, const int32_t *__restrict__ seg_expert,
-    const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm, int M, int N, int k, int d, int F,
-    float *__restrict__ y) {
+    const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm, int n_seg, int M, int N, int k, int d,
+    int F, float *__restrict__ y) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
-  const int seg = blockIdx.y;
+  int seg, tile;
+  xcd_item((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg, seg, tile);
+  if (seg < 0) return;
   const int e = seg_expert[seg];
   const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
   if (!segment_ok(e, beg, m, M, N, k)) return;
   const int wave = threadIdx.x >> 6;
-  int j0 = (blockIdx.x * kFfnWaves + wave) * 32;
+  int j0 = (tile * kFfnWaves + wave) * 32;
   j0 = j0 < d ? j0 : d - 32;  // see ffn_gateup_lds_kernel
   const uint16_t *wt0 = w_down + ((size_t)e * d + j0) * F;
   const uint16_t *wt1 = wt0 + (size_t)16 * F;
-  const int ks = k_stagger(blockIdx.y * gridDim.x + blockIdx.x, F);
+  const int ks = k_stagger(seg, F);
   for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
     const int mc = m - c0;
     if (mc <= 16) down_lds<1, 4>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
@@ -538,16 +555,16 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
     for (int pass = 1; pass <= 2; ++pass) {
       if ((pass == 1 ? d : F) % 128 == 0) {
         if (pass == 1) {
-          dim3 grid((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg);
+          const int grid = xcd_grid((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg);
           ffn_gateup_lds_kernel<<<grid, kFfnThreads, 0, st>>>(
               static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(wt.w_gate),
-              static_cast<const uint16_t *>(wt.w_up), seg_expert, seg_off, perm, M, ds.n_experts, k, d, F,
+              static_cast<const uint16_t *>(wt.w_up), seg_expert, seg_off, perm, n_seg, M, ds.n_experts, k, d, F,
               static_cast<uint16_t *>(act));
         } else {
-          dim3 grid((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg);
+          const int grid = xcd_grid((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg);
           ffn_down_lds_kernel<<<grid, kFfnThreads, 0, st>>>(static_cast<const uint16_t *>(act),
                                                             static_cast<const uint16_t *>(wt.w_down), seg_expert,
-                                                            seg_off, perm, M, ds.n_experts, k, d, F, y);
+                                                            seg_off, perm, n_seg, M, ds.n_experts, k, d, F, y);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         mark(pass - 1);
