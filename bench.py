@@ -39,7 +39,8 @@ def parse_args():
     ap.add_argument("--sweep-steps", type=int, default=60)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-tokens", type=int, default=16, help="tree tokens the CPU oracle is timed on")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="minimum host time spent in the CPU oracle (whole layers, one weight set after another)")
     return ap.parse_args()
 
 
@@ -185,19 +186,21 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = 1
-        Wh = {key: (val.float().cpu().numpy() if val.dtype == torch.bfloat16 else val.cpu().numpy())
-              for key, val in sets[0].items()}
+        pol = O.SUBSTITUTE if policy == mb.SUBSTITUTE else O.TRUNCATE
         hh = h.float().cpu().numpy()
-        toks = list(range(min(args.cpu_tokens, M)))
-        t0 = time.perf_counter()
-        O.layer_forward(hh, Wh, cfg.top_k, cfg.renorm, B, O.SUBSTITUTE if policy == mb.SUBSTITUTE else O.TRUNCATE,
-                        tokens=toks)
-        dt = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": round(len(toks) / dt, 3), "unit": "tokens/s", "cores": int(cores),
+        layers, spent = 0, 0.0
+        while spent < args.cpu_seconds and layers < 4 * len(sets):
+            W = sets[layers % len(sets)]
+            Wh = {key: (val.float().cpu().numpy() if val.dtype == torch.bfloat16 else val.cpu().numpy())
+                  for key, val in W.items()}
+            t0 = time.perf_counter()
+            O.layer_forward(hh, Wh, cfg.top_k, cfg.renorm, B, pol)
+            spent += time.perf_counter() - t0
+            layers += 1
+            del Wh
+        result["cpu_baseline"] = {"value": round(layers * M / spent, 3), "unit": "tokens/s", "cores": int(cores),
                                   "kind": "oracle",
-                                  "sample": f"routing of all {M} tokens + expert outputs of the first {len(toks)} "
-                                            f"tokens of one layer ({dt:.1f} s, fp64 numpy)"}
-        del Wh
+                                  "sample": f"{layers} whole layers (all {M} tokens, B={B}, fp64 numpy) in {spent:.1f} s"}
 
     print(json.dumps(result))
 
