@@ -99,7 +99,7 @@ moespec_status moespec_budget(const moespec_desc *desc, const double *probs, int
   if (!probs || !tok_ids || !tok_w || !seg_expert || !seg_off || !perm) return MOESPEC_ERR_INVALID_ARG;
   Workspace w = carve_workspace(*desc, M, ws);
   return from_hip(launch_budget(*desc, probs, M, B, policy, ext_shortlist, scores, budget_ids, tok_ids, tok_w,
-                                seg_expert, seg_off, perm, n_loaded, w.done, false,
+                                seg_expert, seg_off, perm, n_loaded, w.items, w.done, false,
                                 static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -115,7 +115,7 @@ moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weight
   if (!aligned16(h) || !aligned16(out) || (residual && !aligned16(residual))) return MOESPEC_ERR_INVALID_ARG;
   Workspace w = carve_workspace(*desc, M, ws);
   return from_hip(launch_expert_ffn(*desc, *weights, h, M, n_seg, seg_expert, seg_off, perm, tok_ids, tok_w, residual,
-                                    out, w.act, w.y, static_cast<hipStream_t>(hip_stream)));
+                                    out, w.act, w.y, w.items, false, static_cast<hipStream_t>(hip_stream)));
 }
 
 moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_weights *weights, const void *h,
@@ -147,11 +147,11 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(1);
   e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, t.budget_ids, tok_ids, tok_w, seg_expert,
-                    seg_off, perm, t.n_loaded, w.done, true, st);
+                    seg_off, perm, t.n_loaded, w.items, w.done, true, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(2);
   e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
-                        w.y, st, tr ? tr + 3 : nullptr);
+                        w.y, w.items, true, st, tr ? tr + 3 : nullptr);
   return from_hip(e);
 }
 

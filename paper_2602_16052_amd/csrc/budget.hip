@@ -25,12 +25,16 @@ __device__ __forceinline__ double column_sum(const double *__restrict__ probs, i
 // Groups the surviving (token, slot) pairs by expert: segment i holds the pairs routed to
 // seg_expert[i], tokens ascending.  Run by one whole workgroup; one wave per segment at a time,
 // 64 tokens per ballot.  The routing table is staged in LDS slot-major (lanes read consecutive
-// words) when it fits.  lds: (2 B + 1 + (staged ? M k : 0)) int32.
+// words) when it fits.  items[0].x receives the number L of non-empty segments and items[1 + r]
+// (segment, expert, offset, size) of the one with rank r when they are ordered by size, largest
+// first (ties: lower segment first) - the order in which the expert passes hand them out.
+// lds: (3 B + 1 + (staged ? M k : 0)) int32.
 __device__ void build_segments(const int32_t *tok_ids, int M, int k, int B, int staged, const int32_t *seg_expert,
-                               int32_t *seg_off, int32_t *perm, int32_t *n_loaded, int32_t *lds) {
-  int32_t *cnt = lds;           // [B + 1] counts, then exclusive offsets
+                               int32_t *seg_off, int32_t *perm, int32_t *n_loaded, int4 *items, int32_t *lds) {
+  int32_t *cnt = lds;           // [B + 1] exclusive offsets
   int32_t *sexp = cnt + B + 1;  // [B] seg_expert
-  int32_t *copy = sexp + B;     // [k][M] routing table, slot-major (if staged)
+  int32_t *sz = sexp + B;       // [B] sizes
+  int32_t *copy = sz + B;       // [k][M] routing table, slot-major (if staged)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwave = blockDim.x >> 6;
   for (int i = tid; i < B; i += blockDim.x) sexp[i] = seg_expert[i];
   if (staged)
@@ -48,23 +52,43 @@ __device__ void build_segments(const int32_t *tok_ids, int M, int k, int B, int 
         for (int j = 0; j < k; ++j) has |= (id_at(t, j) == e);
       c += __popcll(__ballot(has));
     }
-    if (lane == 0) cnt[i] = c;
+    if (lane == 0) sz[i] = c;
   }
   __syncthreads();
-  if (tid == 0) {
+  if (wave == 0) {  // exclusive scan of the sizes, 64 segments per step
     int run = 0, loaded = 0;
-    for (int i = 0; i < B; ++i) {
-      const int c = cnt[i];
-      seg_off[i] = run;
-      cnt[i] = run;
-      run += c;
-      loaded += (c > 0);
+    for (int i0 = 0; i0 < B; i0 += kWave) {
+      const int i = i0 + lane;
+      const int c = i < B ? sz[i] : 0;
+      int incl = c;
+#pragma unroll
+      for (int sft = 1; sft < kWave; sft <<= 1) {
+        const int v = __shfl_up(incl, sft, kWave);
+        if (lane >= sft) incl += v;
+      }
+      if (i < B) {
+        seg_off[i] = run + incl - c;
+        cnt[i] = run + incl - c;
+      }
+      run += __shfl(incl, kWave - 1, kWave);
+      loaded += __popcll(__ballot(c > 0));
     }
-    seg_off[B] = run;
-    if (n_loaded) *n_loaded = loaded;
-    cnt[B] = run;
+    if (lane == 0) {
+      seg_off[B] = run;
+      items[0] = int4{loaded, 0, 0, 0};
+      if (n_loaded) *n_loaded = loaded;
+      cnt[B] = run;
+    }
   }
   __syncthreads();
+  for (int i = tid; i < B; i += blockDim.x) {
+    const int c = sz[i];
+    if (c > 0) {
+      int r = 0;
+      for (int j = 0; j < B; ++j) r += (sz[j] > c || (sz[j] == c && j < i)) ? 1 : 0;
+      items[1 + r] = int4{i, sexp[i], cnt[i], c};
+    }
+  }
   const int P = cnt[B];
   for (int p = P + tid; p < M * k; p += blockDim.x) perm[p] = -1;
   for (int i = wave; i < B; i += nwave) {
@@ -90,7 +114,8 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
     const double *__restrict__ probs, int M, int N, int k, int B, int policy, int renorm,
     const int32_t *__restrict__ ext_shortlist, double *__restrict__ scores, int32_t *__restrict__ budget_ids,
     int32_t *__restrict__ seg_expert, int32_t *tok_ids, float *__restrict__ tok_w, int32_t *__restrict__ seg_off,
-    int32_t *__restrict__ perm, int32_t *__restrict__ n_loaded, int staged, int32_t *done) {
+    int32_t *__restrict__ perm, int32_t *__restrict__ n_loaded, int4 *__restrict__ items, int staged,
+    int32_t *done) {
   extern __shared__ __align__(16) unsigned char smem[];
   double *s = reinterpret_cast<double *>(smem);                  // [N] aggregate scores
   double *g = s + N;                                              // [N] this token's probabilities
@@ -181,7 +206,8 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
   const bool last = *flag != 0;
   __syncthreads();  // everybody has read the flag before the LDS is reused below
   if (!last) return;
-  build_segments(tok_ids, M, k, B, staged, seg_expert, seg_off, perm, n_loaded, reinterpret_cast<int32_t *>(smem));
+  build_segments(tok_ids, M, k, B, staged, seg_expert, seg_off, perm, n_loaded, items,
+                 reinterpret_cast<int32_t *>(smem));
 }
 
 __global__ void zero_words_kernel(int32_t *p, int n) {
@@ -191,7 +217,7 @@ __global__ void zero_words_kernel(int32_t *p, int n) {
 hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
                          const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
-                         int32_t *done, bool done_is_zero, hipStream_t st) {
+                         int4 *items, int32_t *done, bool done_is_zero, hipStream_t st) {
   const int N = ds.n_experts, k = ds.top_k;
   if (!done_is_zero) {
     zero_words_kernel<<<1, 64, 0, st>>>(done, 1);
@@ -200,10 +226,10 @@ hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int
   }
   const int staged = (size_t)M * k <= 8192;
   const size_t smem_sel = sizeof(double) * (2 * N + ((k + 1) & ~1) + 2) + sizeof(int32_t) * (k + B + N + 1) + N;
-  const size_t smem_seg = sizeof(int32_t) * (2 * B + 1 + (staged ? (size_t)M * k : 0));
+  const size_t smem_seg = sizeof(int32_t) * (3 * B + 1 + (staged ? (size_t)M * k : 0));
   budget_kernel<<<M, kBudgetThreads, smem_sel > smem_seg ? smem_sel : smem_seg, st>>>(
       probs, M, N, k, B, policy, ds.renorm, ext_shortlist, scores, budget_ids, seg_expert, tok_ids, tok_w, seg_off, perm,
-      n_loaded, staged, done);
+      n_loaded, items, staged, done);
   return hipGetLastError();
 }
 

@@ -119,6 +119,7 @@ struct Workspace {
   int32_t *seg_expert;  // [N]
   int32_t *seg_off;   // [N + 1]
   int32_t *perm;      // [M * k]
+  int4 *items;        // [N + 1] count, then (segment, expert, offset, size) of the non-empty segments
   int32_t *n_loaded;  // [1]
   int32_t *done;      // [1] ticket counter of the budget stage
   void *act;          // [M * k, F] dtype
@@ -145,6 +146,7 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
   w.seg_expert = static_cast<int32_t *>(take(sizeof(int32_t) * N));
   w.seg_off = static_cast<int32_t *>(take(sizeof(int32_t) * (N + 1)));
   w.perm = static_cast<int32_t *>(take(sizeof(int32_t) * M * k));
+  w.items = static_cast<int4 *>(take(sizeof(int4) * (N + 1)));
   w.n_loaded = static_cast<int32_t *>(take(sizeof(int32_t)));
   w.done = static_cast<int32_t *>(take(sizeof(int32_t)));
   w.act = take(es * M * k * F);
@@ -160,11 +162,13 @@ hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const
 hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
                          const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
-                         int32_t *done, bool done_is_zero, hipStream_t st);
+                         int4 *items, int32_t *done, bool done_is_zero, hipStream_t st);
+// items: table of the non-empty segments ([n_seg + 1] int4 of scratch); items_ready says that the budget
+// stage has already filled it from the same segment arrays, otherwise it is built first.
 // trace (may be NULL): 3 events recorded after the gate/up pass, the down pass and the combine.
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
-                             float *y, hipStream_t st, void *const *trace = nullptr);
+                             float *y, int4 *items, bool items_ready, hipStream_t st, void *const *trace = nullptr);
 
 }  // namespace moespec

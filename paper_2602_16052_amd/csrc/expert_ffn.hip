@@ -93,13 +93,45 @@ __device__ __forceinline__ void stream_rows(const uint16_t *a0, const uint16_t *
 // round-robin by linear id, and each XCD has an L2 of its own: all row tiles of one segment are given
 // ids that are equal modulo 8, so that a segment's token rows are fetched into one L2 and then hit
 // there by the other workgroups of the segment (which start together and walk K in the same order).
+// Only non-empty segments take part, largest first: the r-th of them goes to XCD r % 8 in round r / 8.
+// Measured on an idle chip, an XCD places its workgroups on its 32 compute units round-robin in id
+// order, two per unit, and a workgroup with many token tiles runs slower than one with few (more LDS
+// and matrix work per weight byte); in this order the heavy workgroups of the first rounds share
+// their compute unit with the light ones of the later rounds, or with nothing.
+// items[0].x = number of non-empty segments L; items[1 + r] = (segment index, expert, offset, size)
+// of the r-th largest non-empty segment.  The table has n_seg + 1 entries.
 constexpr int kXcds = 8;
-__device__ __forceinline__ void xcd_item(int tiles, int n_seg, int &seg, int &tile) {
+__device__ __forceinline__ int4 xcd_item(int tiles, int n_seg, const int4 *__restrict__ items, int &tile, int &rank) {
   const int bid = blockIdx.x, slot = bid / kXcds;
-  seg = bid % kXcds + kXcds * (slot / tiles);
+  rank = bid % kXcds + kXcds * (slot / tiles);
   tile = slot % tiles;
-  if (seg >= n_seg) seg = -1;
+  int L = items[0].x;
+  L = L > n_seg ? n_seg : L;
+  return rank < L ? items[1 + rank] : int4{-1, -1, 0, 0};
 }
+// The table above built from segment arrays that did not come from the budget stage.  One workgroup.
+__global__ __launch_bounds__(256) void segment_items_kernel(const int32_t *__restrict__ seg_expert,
+                                                            const int32_t *__restrict__ seg_off, int n_seg,
+                                                            int4 *__restrict__ items) {
+  __shared__ int n_nonempty;
+  if (threadIdx.x == 0) n_nonempty = 0;
+  __syncthreads();
+  for (int i = threadIdx.x; i < n_seg; i += blockDim.x) {
+    const int lo = seg_off[i], c = seg_off[i + 1] - lo;
+    if (c > 0) {
+      int r = 0;
+      for (int j = 0; j < n_seg; ++j) {
+        const int cj = seg_off[j + 1] - seg_off[j];
+        r += (cj > c || (cj == c && j < i)) ? 1 : 0;
+      }
+      items[1 + r] = int4{i, seg_expert[i], lo, c};
+      atomicAdd(&n_nonempty, 1);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) items[0] = int4{n_nonempty, 0, 0, 0};
+}
+// Workgroups of a pass: whole rounds of 8 segments.
 inline int xcd_grid(int tiles, int n_seg) { return kXcds * tiles * ((n_seg + kXcds - 1) / kXcds); }
 
 // Start offset (elements) of a wave's walk over K: 128 elements (256 bytes) apart for consecutive waves.
@@ -344,15 +376,13 @@ __device__ __forceinline__ void gateup_lds(const uint16_t *wt0, const uint16_t *
 
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
     const uint16_t *__restrict__ h, const uint16_t *__restrict__ w_gate, const uint16_t *__restrict__ w_up,
-    const int32_t *__restrict__ seg_expert, const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm,
-    int n_seg, int M, int N, int k, int d, int F, uint16_t *__restrict__ act) {
+    const int4 *__restrict__ items, const int32_t *__restrict__ perm, int n_seg, int M, int N, int k, int d, int F,
+    uint16_t *__restrict__ act) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
-  int seg, tile;
-  xcd_item((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg, seg, tile);
-  if (seg < 0) return;
-  const int e = seg_expert[seg];
-  const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
-  if (!segment_ok(e, beg, m, M, N, k)) return;
+  int tile, rank;
+  const int4 it = xcd_item((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg, items, tile, rank);
+  const int seg = it.x, e = it.y, beg = it.z, m = it.w;
+  if (seg < 0 || !segment_ok(e, beg, m, M, N, k)) return;
   const int wave = threadIdx.x >> 6;
   // F is a multiple of 32 but a workgroup covers 64 gate rows: the waves of a last, partial workgroup
   // redo rows of the previous tile (same values, same destination) so that every wave reaches the barriers.
@@ -360,7 +390,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
   f0 = f0 < F ? f0 : F - 16;
   const uint16_t *wt0 = w_gate + ((size_t)e * F + f0) * d;
   const uint16_t *wt1 = w_up + ((size_t)e * F + f0) * d;
-  const int ks = k_stagger(seg, d);
+    const int ks = k_stagger(rank, d);
   for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
     const int mc = m - c0;
     if (mc <= 16) gateup_lds<1, 4>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
@@ -402,22 +432,19 @@ __device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt
 }
 
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
-    const uint16_t *__restrict__ act, const uint16_t *__restrict__ w_down, const int32_t *__restrict__ seg_expert,
-    const int32_t *__restrict__ seg_off, const int32_t *__restrict__ perm, int n_seg, int M, int N, int k, int d,
-    int F, float *__restrict__ y) {
+    const uint16_t *__restrict__ act, const uint16_t *__restrict__ w_down, const int4 *__restrict__ items,
+    const int32_t *__restrict__ perm, int n_seg, int M, int N, int k, int d, int F, float *__restrict__ y) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
-  int seg, tile;
-  xcd_item((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg, seg, tile);
-  if (seg < 0) return;
-  const int e = seg_expert[seg];
-  const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
-  if (!segment_ok(e, beg, m, M, N, k)) return;
+  int tile, rank;
+  const int4 it = xcd_item((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg, items, tile, rank);
+  const int seg = it.x, e = it.y, beg = it.z, m = it.w;
+  if (seg < 0 || !segment_ok(e, beg, m, M, N, k)) return;
   const int wave = threadIdx.x >> 6;
   int j0 = (tile * kFfnWaves + wave) * 32;
   j0 = j0 < d ? j0 : d - 32;  // see ffn_gateup_lds_kernel
   const uint16_t *wt0 = w_down + ((size_t)e * d + j0) * F;
   const uint16_t *wt1 = wt0 + (size_t)16 * F;
-  const int ks = k_stagger(seg, F);
+    const int ks = k_stagger(rank, F);
   for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
     const int mc = m - c0;
     if (mc <= 16) down_lds<1, 4>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
@@ -545,9 +572,13 @@ static int pick_unroll(int K) { return K % 128 == 0 ? 4 : (K % 64 == 0 ? 2 : 1);
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
-                             float *y, hipStream_t st, void *const *trace) {
+                             float *y, int4 *items, bool items_ready, hipStream_t st, void *const *trace) {
   const int d = ds.d, F = ds.d_ff, k = ds.top_k;
   hipError_t e;
+  if (ds.dtype == MOESPEC_BF16 && !items_ready && (d % 128 == 0 || F % 128 == 0)) {
+    segment_items_kernel<<<1, 256, 0, st>>>(seg_expert, seg_off, n_seg, items);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   auto mark = [&](int i) {
     if (trace && trace[i]) (void)hipEventRecord(static_cast<hipEvent_t>(trace[i]), st);
   };
@@ -558,13 +589,13 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
           const int grid = xcd_grid((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg);
           ffn_gateup_lds_kernel<<<grid, kFfnThreads, 0, st>>>(
               static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(wt.w_gate),
-              static_cast<const uint16_t *>(wt.w_up), seg_expert, seg_off, perm, n_seg, M, ds.n_experts, k, d, F,
+              static_cast<const uint16_t *>(wt.w_up), items, perm, n_seg, M, ds.n_experts, k, d, F,
               static_cast<uint16_t *>(act));
         } else {
           const int grid = xcd_grid((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg);
           ffn_down_lds_kernel<<<grid, kFfnThreads, 0, st>>>(static_cast<const uint16_t *>(act),
-                                                            static_cast<const uint16_t *>(wt.w_down), seg_expert,
-                                                            seg_off, perm, n_seg, M, ds.n_experts, k, d, F, y);
+                                                            static_cast<const uint16_t *>(wt.w_down), items, perm,
+                                                            n_seg, M, ds.n_experts, k, d, F, y);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         mark(pass - 1);
