@@ -86,7 +86,7 @@ moespec_status moespec_route(const moespec_desc *desc, const moespec_weights *we
   if ((s = check_weights(weights, true, false)) != MOESPEC_OK) return s;
   if (!h || !probs || !aligned16(h)) return MOESPEC_ERR_INVALID_ARG;
   return from_hip(
-      launch_route(*desc, *weights, h, M, probs, topk_ids, topk_w, nullptr, static_cast<hipStream_t>(hip_stream)));
+      launch_route(*desc, *weights, h, M, probs, topk_ids, topk_w, nullptr, 0, static_cast<hipStream_t>(hip_stream)));
 }
 
 moespec_status moespec_budget(const moespec_desc *desc, const double *probs, int32_t M, int32_t B, int32_t policy,
@@ -98,8 +98,9 @@ moespec_status moespec_budget(const moespec_desc *desc, const double *probs, int
   if ((s = check_budget(desc, B, policy)) != MOESPEC_OK) return s;
   if (!probs || !tok_ids || !tok_w || !seg_expert || !seg_off || !perm) return MOESPEC_ERR_INVALID_ARG;
   Workspace w = carve_workspace(*desc, M, ws);
-  return from_hip(launch_budget(*desc, probs, M, B, policy, ext_shortlist, scores, budget_ids, tok_ids, tok_w,
-                                seg_expert, seg_off, perm, n_loaded, w.items, w.done, false,
+  return from_hip(launch_budget(*desc, probs, M, B, policy, ext_shortlist, scores,
+                                budget_ids ? budget_ids : w.budget_ids, tok_ids, tok_w,
+                                seg_expert, seg_off, perm, n_loaded, w.items, w.done, false, true,
                                 static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -115,7 +116,8 @@ moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weight
   if (!aligned16(h) || !aligned16(out) || (residual && !aligned16(residual))) return MOESPEC_ERR_INVALID_ARG;
   Workspace w = carve_workspace(*desc, M, ws);
   return from_hip(launch_expert_ffn(*desc, *weights, h, M, n_seg, seg_expert, seg_off, perm, tok_ids, tok_w, residual,
-                                    out, w.act, w.y, w.items, false, static_cast<hipStream_t>(hip_stream)));
+                                    out, w.act, w.y, w.items, false, nullptr, nullptr,
+                                    static_cast<hipStream_t>(hip_stream)));
 }
 
 moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_weights *weights, const void *h,
@@ -138,20 +140,26 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
   int32_t *seg_expert = t.seg_expert ? t.seg_expert : w.seg_expert;
   int32_t *seg_off = t.seg_off ? t.seg_off : w.seg_off;
   int32_t *perm = t.perm ? t.perm : w.perm;
+  int32_t *budget_ids = t.budget_ids ? t.budget_ids : w.budget_ids;
   void *const *tr = t.trace_events;
   auto mark = [&](int i) {
     if (tr && tr[i]) (void)hipEventRecord(static_cast<hipEvent_t>(tr[i]), st);
   };
+  // Small trees: the expert passes derive their segments themselves, and the budget stage groups the
+  // pairs only if the caller asked for the segment arrays.
+  const bool self_seg = expert_ffn_self_segmenting(*desc, M);
+  const bool want_segments = !self_seg || t.seg_off || t.perm || t.n_loaded;
   mark(0);
-  hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, w.done, st);
+  hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, w.done, 1 + desc->n_experts, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(1);
-  e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, t.budget_ids, tok_ids, tok_w, seg_expert,
-                    seg_off, perm, t.n_loaded, w.items, w.done, true, st);
+  e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, budget_ids, tok_ids, tok_w, seg_expert,
+                    seg_off, perm, t.n_loaded, w.items, w.done, true, want_segments, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(2);
   e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
-                        w.y, w.items, true, st, tr ? tr + 3 : nullptr);
+                        w.y, w.items, want_segments, self_seg ? w.done + 1 : nullptr, budget_ids, st,
+                        tr ? tr + 3 : nullptr);
   return from_hip(e);
 }
 

@@ -109,13 +109,15 @@ __device__ void build_segments(const int32_t *tok_ids, int M, int k, int B, int 
 
 // One workgroup per tree token.  Every workgroup recomputes the (tiny) scores and shortlist so that
 // no grid-wide synchronisation is needed; workgroup 0 also writes them out.  The workgroup that
-// finishes last (ticket counter `done`, zero at launch) builds the segments from everybody's rows.
+// finishes last (ticket counter done[0], zero at launch) builds the segments from everybody's rows,
+// if they are wanted.  done[1 + r] (zero at launch) receives the number of surviving pairs of the expert
+// with shortlist rank r.
 __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
     const double *__restrict__ probs, int M, int N, int k, int B, int policy, int renorm,
     const int32_t *__restrict__ ext_shortlist, double *__restrict__ scores, int32_t *__restrict__ budget_ids,
     int32_t *__restrict__ seg_expert, int32_t *tok_ids, float *__restrict__ tok_w, int32_t *__restrict__ seg_off,
     int32_t *__restrict__ perm, int32_t *__restrict__ n_loaded, int4 *__restrict__ items, int staged,
-    int32_t *done) {
+    int want_segments, int32_t *done) {
   extern __shared__ __align__(16) unsigned char smem[];
   double *s = reinterpret_cast<double *>(smem);                  // [N] aggregate scores
   double *g = s + N;                                              // [N] this token's probabilities
@@ -123,7 +125,8 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
   int32_t *sel = reinterpret_cast<int32_t *>(wsel + ((k + 1) & ~1) + 2);  // [k]
   int32_t *S = sel + k;                                           // [B] shortlist in rank order
   int32_t *rank = S + B;                                          // [N] scratch of the selections
-  int32_t *flag = rank + N;                                       // [1] "this workgroup is the last one"
+  int32_t *pos = rank + N;                                        // [N] shortlist rank of every expert
+  int32_t *flag = pos + N;                                        // [1] "this workgroup is the last one"
   uint8_t *inS = reinterpret_cast<uint8_t *>(flag + 1);           // [N] membership
 
   const int t = blockIdx.x, tid = threadIdx.x;
@@ -131,6 +134,7 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
   for (int i = tid; i < N; i += blockDim.x) {
     g[i] = probs[(size_t)t * N + i];
     inS[i] = 0;
+    pos[i] = 0x7fffffff;
   }
   if (ext_shortlist == nullptr) {
     // Eq. (5): s_i = sum over the M tree tokens of g_i(h_t), tokens in ascending order.
@@ -144,7 +148,10 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
   }
   __syncthreads();
   for (int r = tid; r < B; r += blockDim.x)
-    if ((uint32_t)S[r] < (uint32_t)N) inS[S[r]] = 1;  // ids outside [0, N) in an external shortlist are ignored
+    if ((uint32_t)S[r] < (uint32_t)N) {  // ids outside [0, N) in an external shortlist are ignored
+      inS[S[r]] = 1;
+      atomicMin(&pos[S[r]], r);  // an expert named twice counts at its first rank
+    }
   __syncthreads();
 
   if (t == 0) {
@@ -161,7 +168,7 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
       for (int j = 0; j < N; ++j) n_member += inS[j];
       for (int r = tid; r < B; r += blockDim.x) {
         if (r >= n_member) seg_expert[r] = -1;
-        if (budget_ids) budget_ids[r] = S[r];
+        budget_ids[r] = S[r];
       }
     }
   }
@@ -176,6 +183,7 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
       const bool keep = inS[sel[j]] != 0;
       tok_ids[(size_t)t * k + j] = keep ? sel[j] : -1;
       tok_w[(size_t)t * k + j] = keep ? (float)wsel[j] : 0.0f;
+      if (keep) atomicAdd(&done[1 + pos[sel[j]]], 1);
     }
   } else {
     // Top-k inside S by g_i(h_t); weights over the constrained selection.  Slots stay unfilled (-1)
@@ -189,9 +197,11 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
     for (int j = tid; j < k; j += blockDim.x) {
       tok_ids[(size_t)t * k + j] = sel[j];
       tok_w[(size_t)t * k + j] = (float)wsel[j];
+      if (sel[j] >= 0) atomicAdd(&done[1 + pos[sel[j]]], 1);
     }
   }
 
+  if (!want_segments) return;
   // Last workgroup to arrive groups the pairs of all tokens.  One thread publishes the workgroup's
   // rows (the barrier before it orders everybody's stores first) and takes the ticket; device-scope
   // fences are expensive, so they are not executed by every wave.
@@ -217,19 +227,19 @@ __global__ void zero_words_kernel(int32_t *p, int n) {
 hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
                          const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
-                         int4 *items, int32_t *done, bool done_is_zero, hipStream_t st) {
+                         int4 *items, int32_t *done, bool done_is_zero, bool want_segments, hipStream_t st) {
   const int N = ds.n_experts, k = ds.top_k;
   if (!done_is_zero) {
-    zero_words_kernel<<<1, 64, 0, st>>>(done, 1);
+    zero_words_kernel<<<1, 256, 0, st>>>(done, 1 + N);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   const int staged = (size_t)M * k <= 8192;
-  const size_t smem_sel = sizeof(double) * (2 * N + ((k + 1) & ~1) + 2) + sizeof(int32_t) * (k + B + N + 1) + N;
+  const size_t smem_sel = sizeof(double) * (2 * N + ((k + 1) & ~1) + 2) + sizeof(int32_t) * (k + B + 2 * N + 1) + N;
   const size_t smem_seg = sizeof(int32_t) * (3 * B + 1 + (staged ? (size_t)M * k : 0));
   budget_kernel<<<M, kBudgetThreads, smem_sel > smem_seg ? smem_sel : smem_seg, st>>>(
       probs, M, N, k, B, policy, ds.renorm, ext_shortlist, scores, budget_ids, seg_expert, tok_ids, tok_w, seg_off, perm,
-      n_loaded, items, staged, done);
+      n_loaded, items, staged, want_segments ? 1 : 0, done);
   return hipGetLastError();
 }
 

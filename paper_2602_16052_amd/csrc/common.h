@@ -121,7 +121,7 @@ struct Workspace {
   int32_t *perm;      // [M * k]
   int4 *items;        // [N + 1] count, then (segment, expert, offset, size) of the non-empty segments
   int32_t *n_loaded;  // [1]
-  int32_t *done;      // [1] ticket counter of the budget stage
+  int32_t *done;      // [1 + N] ticket counter of the budget stage, then surviving pairs per shortlist rank
   void *act;          // [M * k, F] dtype
   float *y;           // [M * k, d]
   size_t bytes;
@@ -148,7 +148,7 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
   w.perm = static_cast<int32_t *>(take(sizeof(int32_t) * M * k));
   w.items = static_cast<int4 *>(take(sizeof(int4) * (N + 1)));
   w.n_loaded = static_cast<int32_t *>(take(sizeof(int32_t)));
-  w.done = static_cast<int32_t *>(take(sizeof(int32_t)));
+  w.done = static_cast<int32_t *>(take(sizeof(int32_t) * (1 + N)));
   w.act = take(es * M * k * F);
   w.y = static_cast<float *>(take(sizeof(float) * M * k * d));
   w.bytes = off;
@@ -156,19 +156,29 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
 }
 
 // Launchers (defined in the .hip files).  Each returns hipGetLastError() after its launches.
-// zero_word (may be NULL): one int32 that the kernel sets to 0 (the ticket counter of the budget stage).
+// zero_words (may be NULL): n_zero int32 that the route stage sets to 0 (the counters of the budget stage).
 hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *probs,
-                        int32_t *topk_ids, float *topk_w, int32_t *zero_word, hipStream_t st);
+                        int32_t *topk_ids, float *topk_w, int32_t *zero_words, int n_zero, hipStream_t st);
+// done: [1 + N] counters (ticket, then the number of surviving pairs of the expert at each shortlist
+// rank), zero at launch or zeroed first (done_is_zero == false).  budget_ids must not be NULL.
+// want_segments == false skips seg_off / perm / n_loaded / items: the expert passes can then only run in
+// the mode that derives its segments from done + 1, budget_ids and tok_ids.
 hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
                          const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
-                         int4 *items, int32_t *done, bool done_is_zero, hipStream_t st);
+                         int4 *items, int32_t *done, bool done_is_zero, bool want_segments, hipStream_t st);
 // items: table of the non-empty segments ([n_seg + 1] int4 of scratch); items_ready says that the budget
 // stage has already filled it from the same segment arrays, otherwise it is built first.
+// rank_count, shortlist (may be NULL): the shortlist in rank order ([n_seg]) and the surviving pairs of each
+// of its experts, from the budget stage; when given and the shape allows (expert_ffn_self_segmenting),
+// every workgroup derives its segment from them and tok_ids itself, and seg_expert / seg_off / perm /
+// items are not read.
 // trace (may be NULL): 3 events recorded after the gate/up pass, the down pass and the combine.
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
-                             float *y, int4 *items, bool items_ready, hipStream_t st, void *const *trace = nullptr);
+                             float *y, int4 *items, bool items_ready, const int32_t *rank_count,
+                             const int32_t *shortlist, hipStream_t st, void *const *trace = nullptr);
+bool expert_ffn_self_segmenting(const moespec_desc &ds, int M);
 
 }  // namespace moespec

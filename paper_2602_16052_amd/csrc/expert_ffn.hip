@@ -18,6 +18,12 @@
 // Workgroups start their K walk at staggered offsets: weight rows are a power-of-two stride
 // apart, and equal offsets would pile the concurrent reads onto the same memory channels.
 // Shapes whose K is not a multiple of 128 take a simpler direct-load variant of the same tiling.
+// The intermediate act and the per-pair outputs y are indexed by the flat pair id t * k + slot.
+//
+// Where its segment comes from: either from the segment arrays (seg_expert, seg_off, perm; any
+// caller), or - inside the fused layer, for small trees - every workgroup derives it from the
+// shortlist, the pair count of every shortlisted expert and the restricted routing table, which takes
+// no longer than reading perm and spares the budget stage its serial grouping step.
 #include "common.h"
 
 namespace moespec {
@@ -167,7 +173,7 @@ __device__ __forceinline__ void gateup_tiles(const uint16_t *a0, const uint16_t 
       uint2 pk;
       pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
       pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
-      *reinterpret_cast<uint2 *>(act + (size_t)(beg + p) * F + f0 + 4 * kg) = pk;
+      *reinterpret_cast<uint2 *>(act + (size_t)pair_index(perm, beg + p, M, k) * F + f0 + 4 * kg) = pk;
     }
   }
 }
@@ -209,7 +215,7 @@ __device__ __forceinline__ void down_tiles(const uint16_t *a0, const uint16_t *a
   for (int j = 0; j < NT; ++j) {
     int p = c0 + j * 16 + col;
     p = p < m ? p : m - 1;
-    bp[j] = act + (size_t)(beg + p) * F + kg * 8;
+    bp[j] = act + (size_t)pair_index(perm, beg + p, M, k) * F + kg * 8;
   }
   f32x4 acc0[NT], acc1[NT];
 #pragma unroll
@@ -338,11 +344,72 @@ __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt
   __syncthreads();  // the LDS tiles may be reused by the caller's next pass
 }
 
+// The workgroup's segment derived on the spot (fused layer, small trees).  shortlist[r] = expert with
+// rank r in the shortlist (descending aggregate score, which is also roughly descending segment size),
+// rank_count[r] = number of its surviving pairs, tok_ids = restricted routing table [M, k].  The
+// workgroup takes the `rank`-th shortlisted expert that has pairs and collects them in token order
+// into plist (LDS, up to M entries).  Everything is read in one round of independent loads.
+// Requires B <= kFfnThreads, k <= kSelfMaxK, M <= kSelfMaxTokens.  misc: 8 int32 of LDS scratch.
+// Called by every thread of the workgroup (it synchronises).  Returns the expert (-1: no such rank).
+constexpr int kSelfMaxTokens = 1024;  // plist entries
+constexpr int kSelfMaxK = 16;
+__device__ __forceinline__ int self_segment(const int32_t *__restrict__ rank_count,
+                                            const int32_t *__restrict__ shortlist, int B,
+                                            const int32_t *__restrict__ tok_ids, int M, int k, int rank,
+                                            int32_t *misc, int32_t *plist, int &m) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int ids[kSelfMaxK];
+  auto load_ids = [&](int t) {
+#pragma unroll
+    for (int j = 0; j < kSelfMaxK; ++j) ids[j] = (j < k && t < M) ? tok_ids[(size_t)t * k + j] : -1;
+  };
+  load_ids(tid);
+  const int c = tid < B ? rank_count[tid] : 0;
+  const int ex = tid < B ? shortlist[tid] : -1;
+  const bool nz = c > 0;
+  unsigned long long mask = __ballot(nz);
+  if (lane == 0) misc[1 + wave] = __popcll(mask);
+  if (tid == 0) misc[0] = -1;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < wave; ++w) before += misc[1 + w];
+  if (nz && before + __popcll(mask & ((1ull << lane) - 1ull)) == rank) misc[0] = ex;
+  __syncthreads();
+  const int e = misc[0];
+  m = 0;
+  if (e < 0) return -1;
+  int base = 0;
+  for (int t0 = 0; t0 < M; t0 += kFfnThreads) {  // uniform trip count
+    const int t = t0 + tid;
+    if (t0 > 0) load_ids(t);
+    int slot = -1;
+#pragma unroll
+    for (int j = 0; j < kSelfMaxK; ++j)
+      if (ids[j] == e) slot = j;
+    mask = __ballot(slot >= 0);
+    __syncthreads();  // everybody has read the wave counts of the previous round
+    if (lane == 0) misc[1 + wave] = __popcll(mask);
+    __syncthreads();
+    before = base;
+    for (int w = 0; w < wave; ++w) before += misc[1 + w];
+    if (slot >= 0) plist[before + __popcll(mask & ((1ull << lane) - 1ull))] = t * k + slot;
+    for (int w = 0; w < kFfnWaves; ++w) base += misc[1 + w];
+  }
+  __syncthreads();
+  m = base;
+  return e;
+}
+
+// plist: the segment's pairs (flat ids t * k + slot, tokens ascending), in global memory or LDS; n_pairs = M * k.
+__device__ __forceinline__ int pair_at(const int32_t *plist, int p, int n_pairs) {
+  const int q = plist[p];
+  return q < 0 ? 0 : (q >= n_pairs ? n_pairs - 1 : q);
+}
+
 template <int NT, int U>
 __device__ __forceinline__ void gateup_lds(const uint16_t *wt0, const uint16_t *wt1, const uint16_t *__restrict__ h,
-                                           const int32_t *__restrict__ perm, int M, int k, int d, int F, int beg,
-                                           int c0, int m, int f0, int ks, unsigned char *lds,
-                                           uint16_t *__restrict__ act) {
+                                           const int32_t *plist, int n_pairs, int k, int d, int F, int c0, int m,
+                                           int f0, int ks, unsigned char *lds, uint16_t *__restrict__ act) {
   using C = Chunk<U>;
   constexpr int IPW = NT * U / 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -352,7 +419,7 @@ __device__ __forceinline__ void gateup_lds(const uint16_t *wt0, const uint16_t *
     const int g = (wave * IPW + q) * 64 + lane;
     int p = c0 + g / C::CPR;
     p = p < m ? p : m - 1;  // pad rows repeat the last token; their columns are never stored
-    xsrc[q] = h + (size_t)(pair_index(perm, beg + p, M, k) / k) * d + (g % C::CPR) * 8;
+    xsrc[q] = h + (size_t)(pair_at(plist, p, n_pairs) / k) * d + (g % C::CPR) * 8;
   }
   f32x4 accg[NT], accu[NT];
 #pragma unroll
@@ -369,20 +436,37 @@ __device__ __forceinline__ void gateup_lds(const uint16_t *wt0, const uint16_t *
       uint2 pk;
       pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
       pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
-      *reinterpret_cast<uint2 *>(act + (size_t)(beg + p) * F + f0 + 4 * kg) = pk;
+      *reinterpret_cast<uint2 *>(act + (size_t)pair_at(plist, p, n_pairs) * F + f0 + 4 * kg) = pk;
     }
   }
 }
 
+// rank_count != NULL: self-segmenting mode (items / perm unused; n_seg = B); otherwise items + perm.
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
     const uint16_t *__restrict__ h, const uint16_t *__restrict__ w_gate, const uint16_t *__restrict__ w_up,
-    const int4 *__restrict__ items, const int32_t *__restrict__ perm, int n_seg, int M, int N, int k, int d, int F,
-    uint16_t *__restrict__ act) {
+    const int4 *__restrict__ items, const int32_t *__restrict__ perm, const int32_t *__restrict__ rank_count,
+    const int32_t *__restrict__ shortlist, const int32_t *__restrict__ tok_ids, int n_seg, int M, int N, int k, int d,
+    int F, uint16_t *__restrict__ act) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
-  int tile, rank;
-  const int4 it = xcd_item((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg, items, tile, rank);
-  const int seg = it.x, e = it.y, beg = it.z, m = it.w;
-  if (seg < 0 || !segment_ok(e, beg, m, M, N, k)) return;
+  __shared__ int32_t own_pairs[kSelfMaxTokens];
+  __shared__ int32_t misc[8];
+  const int tiles = (F / 16 + kFfnWaves - 1) / kFfnWaves;
+  int tile, rank, e, m;
+  const int32_t *plist;
+  if (rank_count) {
+    const int slot = blockIdx.x / kXcds;
+    rank = blockIdx.x % kXcds + kXcds * (slot / tiles);
+    tile = slot % tiles;
+    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, rank, misc, own_pairs, m);
+    if (e < 0 || e >= N || m <= 0) return;
+    plist = own_pairs;
+  } else {
+    const int4 it = xcd_item(tiles, n_seg, items, tile, rank);
+    e = it.y;
+    m = it.w;
+    if (it.x < 0 || !segment_ok(e, it.z, m, M, N, k)) return;
+    plist = perm + it.z;
+  }
   const int wave = threadIdx.x >> 6;
   // F is a multiple of 32 but a workgroup covers 64 gate rows: the waves of a last, partial workgroup
   // redo rows of the previous tile (same values, same destination) so that every wave reaches the barriers.
@@ -390,20 +474,21 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
   f0 = f0 < F ? f0 : F - 16;
   const uint16_t *wt0 = w_gate + ((size_t)e * F + f0) * d;
   const uint16_t *wt1 = w_up + ((size_t)e * F + f0) * d;
-    const int ks = k_stagger(rank, d);
+  const int ks = k_stagger(rank, d);
+  const int n_pairs = M * k;
   for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
     const int mc = m - c0;
-    if (mc <= 16) gateup_lds<1, 4>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
-    else if (mc <= 32) gateup_lds<2, 4>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
-    else if (mc <= 64) gateup_lds<4, 4>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
-    else gateup_lds<8, 2>(wt0, wt1, h, perm, M, k, d, F, beg, c0, m, f0, ks, lds, act);
+    if (mc <= 16) gateup_lds<1, 4>(wt0, wt1, h, plist, n_pairs, k, d, F, c0, m, f0, ks, lds, act);
+    else if (mc <= 32) gateup_lds<2, 4>(wt0, wt1, h, plist, n_pairs, k, d, F, c0, m, f0, ks, lds, act);
+    else if (mc <= 64) gateup_lds<4, 4>(wt0, wt1, h, plist, n_pairs, k, d, F, c0, m, f0, ks, lds, act);
+    else gateup_lds<8, 2>(wt0, wt1, h, plist, n_pairs, k, d, F, c0, m, f0, ks, lds, act);
   }
 }
 
 template <int NT, int U>
 __device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt1, const uint16_t *__restrict__ act,
-                                         const int32_t *__restrict__ perm, int M, int k, int d, int F, int beg, int c0,
-                                         int m, int j0, int ks, unsigned char *lds, float *__restrict__ y) {
+                                         const int32_t *plist, int n_pairs, int d, int F, int c0, int m, int j0, int ks,
+                                         unsigned char *lds, float *__restrict__ y) {
   using C = Chunk<U>;
   constexpr int IPW = NT * U / 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -413,7 +498,7 @@ __device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt
     const int g = (wave * IPW + q) * 64 + lane;
     int p = c0 + g / C::CPR;
     p = p < m ? p : m - 1;
-    xsrc[q] = act + (size_t)(beg + p) * F + (g % C::CPR) * 8;
+    xsrc[q] = act + (size_t)pair_at(plist, p, n_pairs) * F + (g % C::CPR) * 8;
   }
   f32x4 acc0[NT], acc1[NT];
 #pragma unroll
@@ -424,7 +509,7 @@ __device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt
   for (int j = 0; j < NT; ++j) {
     const int p = c0 + j * 16 + col;
     if (p < m) {
-      float *dst = y + (size_t)pair_index(perm, beg + p, M, k) * d + j0 + 4 * kg;
+      float *dst = y + (size_t)pair_at(plist, p, n_pairs) * d + j0 + 4 * kg;
       *reinterpret_cast<f32x4 *>(dst) = acc0[j];
       *reinterpret_cast<f32x4 *>(dst + 16) = acc1[j];
     }
@@ -433,24 +518,41 @@ __device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt
 
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
     const uint16_t *__restrict__ act, const uint16_t *__restrict__ w_down, const int4 *__restrict__ items,
-    const int32_t *__restrict__ perm, int n_seg, int M, int N, int k, int d, int F, float *__restrict__ y) {
+    const int32_t *__restrict__ perm, const int32_t *__restrict__ rank_count, const int32_t *__restrict__ shortlist,
+    const int32_t *__restrict__ tok_ids, int n_seg, int M, int N, int k, int d, int F, float *__restrict__ y) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
-  int tile, rank;
-  const int4 it = xcd_item((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg, items, tile, rank);
-  const int seg = it.x, e = it.y, beg = it.z, m = it.w;
-  if (seg < 0 || !segment_ok(e, beg, m, M, N, k)) return;
+  __shared__ int32_t own_pairs[kSelfMaxTokens];
+  __shared__ int32_t misc[8];
+  const int tiles = (d / 32 + kFfnWaves - 1) / kFfnWaves;
+  int tile, rank, e, m;
+  const int32_t *plist;
+  if (rank_count) {
+    const int slot = blockIdx.x / kXcds;
+    rank = blockIdx.x % kXcds + kXcds * (slot / tiles);
+    tile = slot % tiles;
+    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, rank, misc, own_pairs, m);
+    if (e < 0 || e >= N || m <= 0) return;
+    plist = own_pairs;
+  } else {
+    const int4 it = xcd_item(tiles, n_seg, items, tile, rank);
+    e = it.y;
+    m = it.w;
+    if (it.x < 0 || !segment_ok(e, it.z, m, M, N, k)) return;
+    plist = perm + it.z;
+  }
   const int wave = threadIdx.x >> 6;
   int j0 = (tile * kFfnWaves + wave) * 32;
   j0 = j0 < d ? j0 : d - 32;  // see ffn_gateup_lds_kernel
   const uint16_t *wt0 = w_down + ((size_t)e * d + j0) * F;
   const uint16_t *wt1 = wt0 + (size_t)16 * F;
-    const int ks = k_stagger(rank, F);
+  const int ks = k_stagger(rank, F);
+  const int n_pairs = M * k;
   for (int c0 = 0; c0 < m; c0 += 16 * kMaxTiles) {
     const int mc = m - c0;
-    if (mc <= 16) down_lds<1, 4>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
-    else if (mc <= 32) down_lds<2, 4>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
-    else if (mc <= 64) down_lds<4, 4>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
-    else down_lds<8, 2>(wt0, wt1, act, perm, M, k, d, F, beg, c0, m, j0, ks, lds, y);
+    if (mc <= 16) down_lds<1, 4>(wt0, wt1, act, plist, n_pairs, d, F, c0, m, j0, ks, lds, y);
+    else if (mc <= 32) down_lds<2, 4>(wt0, wt1, act, plist, n_pairs, d, F, c0, m, j0, ks, lds, y);
+    else if (mc <= 64) down_lds<4, 4>(wt0, wt1, act, plist, n_pairs, d, F, c0, m, j0, ks, lds, y);
+    else down_lds<8, 2>(wt0, wt1, act, plist, n_pairs, d, F, c0, m, j0, ks, lds, y);
   }
 }
 
@@ -567,15 +669,25 @@ static hipError_t launch_bf16(const moespec_desc &ds, const moespec_weights &wt,
   return hipGetLastError();
 }
 
+// The self-segmenting mode needs both passes on the LDS-tiled kernels and a tree small enough for
+// their LDS scratch.
+bool expert_ffn_self_segmenting(const moespec_desc &ds, int M) {
+  return ds.dtype == MOESPEC_BF16 && ds.d % 128 == 0 && ds.d_ff % 128 == 0 && ds.n_experts <= kFfnThreads &&
+         M <= kSelfMaxTokens && ds.top_k <= kSelfMaxK;
+}
+
 static int pick_unroll(int K) { return K % 128 == 0 ? 4 : (K % 64 == 0 ? 2 : 1); }
 
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
-                             float *y, int4 *items, bool items_ready, hipStream_t st, void *const *trace) {
+                             float *y, int4 *items, bool items_ready, const int32_t *rank_count,
+                             const int32_t *shortlist, hipStream_t st, void *const *trace) {
   const int d = ds.d, F = ds.d_ff, k = ds.top_k;
   hipError_t e;
-  if (ds.dtype == MOESPEC_BF16 && !items_ready && (d % 128 == 0 || F % 128 == 0)) {
+  if (rank_count && !(shortlist && expert_ffn_self_segmenting(ds, M) && n_seg <= kFfnThreads)) rank_count = nullptr;
+  if (!rank_count && !items_ready && !items) return hipErrorInvalidValue;
+  if (ds.dtype == MOESPEC_BF16 && !rank_count && !items_ready && (d % 128 == 0 || F % 128 == 0)) {
     segment_items_kernel<<<1, 256, 0, st>>>(seg_expert, seg_off, n_seg, items);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
@@ -589,13 +701,14 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
           const int grid = xcd_grid((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg);
           ffn_gateup_lds_kernel<<<grid, kFfnThreads, 0, st>>>(
               static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(wt.w_gate),
-              static_cast<const uint16_t *>(wt.w_up), items, perm, n_seg, M, ds.n_experts, k, d, F,
-              static_cast<uint16_t *>(act));
+              static_cast<const uint16_t *>(wt.w_up), items, perm, rank_count, shortlist, tok_ids, n_seg, M,
+              ds.n_experts, k, d, F, static_cast<uint16_t *>(act));
         } else {
           const int grid = xcd_grid((d / 32 + kFfnWaves - 1) / kFfnWaves, n_seg);
           ffn_down_lds_kernel<<<grid, kFfnThreads, 0, st>>>(static_cast<const uint16_t *>(act),
                                                             static_cast<const uint16_t *>(wt.w_down), items, perm,
-                                                            n_seg, M, ds.n_experts, k, d, F, y);
+                                                            rank_count, shortlist, tok_ids, n_seg, M, ds.n_experts,
+                                                            k, d, F, y);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         mark(pass - 1);

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kLogitThreads) void logits_kernel(const T *__restri
 __global__ __launch_bounds__(kSoftmaxThreads) void softmax_topk_kernel(double *__restrict__ probs, int N, int k,
                                                                        int renorm, int32_t *__restrict__ topk_ids,
                                                                        float *__restrict__ topk_w,
-                                                                       int32_t *__restrict__ zero_word) {
+                                                                       int32_t *__restrict__ zero_words, int n_zero) {
   extern __shared__ __align__(16) unsigned char smem[];
   double *g = reinterpret_cast<double *>(smem);               // [N, even] logits, then probabilities
   double *part = g + ((N + 1) & ~1);                          // [32] partial reductions
@@ -79,7 +79,8 @@ __global__ __launch_bounds__(kSoftmaxThreads) void softmax_topk_kernel(double *_
   int32_t *sel = reinterpret_cast<int32_t *>(wsel + ((k + 1) & ~1) + 2);  // [k, multiple of 4]
   int32_t *rank = sel + ((k + 3) & ~3);                       // [N]
   const int t = blockIdx.x, tid = threadIdx.x;
-  if (zero_word && t == 0 && tid == 0) *zero_word = 0;
+  if (zero_words && t == 0)
+    for (int i = tid; i < n_zero; i += blockDim.x) zero_words[i] = 0;
   for (int i = tid; i < N; i += blockDim.x) g[i] = probs[(size_t)t * N + i];
   __syncthreads();
   // 32 strided partial results, then every thread folds the 32 in index order
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(kSoftmaxThreads) void softmax_topk_kernel(double *_
 }
 
 hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *probs,
-                        int32_t *topk_ids, float *topk_w, int32_t *zero_word, hipStream_t st) {
+                        int32_t *topk_ids, float *topk_w, int32_t *zero_words, int n_zero, hipStream_t st) {
   const int N = ds.n_experts, k = ds.top_k, d = ds.d;
   dim3 grid((N + kRowsPerGroup - 1) / kRowsPerGroup, M);
   if (ds.dtype == MOESPEC_BF16) {
@@ -139,7 +140,8 @@ hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const
   if (e != hipSuccess) return e;
   const size_t smem = sizeof(double) * (((N + 1) & ~1) + 32 + ((k + 1) & ~1) + 2) +
                       sizeof(int32_t) * (((k + 3) & ~3) + N);
-  softmax_topk_kernel<<<M, kSoftmaxThreads, smem, st>>>(probs, N, k, ds.renorm, topk_ids, topk_w, zero_word);
+  softmax_topk_kernel<<<M, kSoftmaxThreads, smem, st>>>(probs, N, k, ds.renorm, topk_ids, topk_w, zero_words,
+                                                        n_zero);
   return hipGetLastError();
 }
 

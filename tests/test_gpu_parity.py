@@ -24,6 +24,12 @@ SMALL = {
     "s_bf16_m1": wl.small_config("s_bf16_m1", "bf16", d=64, n_experts=8, top_k=2, d_ff=32, M=1, budgets=(2, 8)),
     "s_bf16_n100": wl.small_config("s_bf16_n100", "bf16", d=320, n_experts=100, top_k=6, d_ff=96, M=70,
                                    budgets=(6, 40, 100), bias_alpha=1.0, renorm=False),
+    # d and F multiples of 128: both expert passes on the LDS-tiled kernels, whose workgroups find their
+    # own segments inside the fused call
+    "s_bf16_self": wl.small_config("s_bf16_self", "bf16", d=256, n_experts=16, top_k=4, d_ff=384, M=45,
+                                   budgets=(4, 9, 16), bias_alpha=0.8),
+    "s_bf16_self_big": wl.small_config("s_bf16_self_big", "bf16", d=128, n_experts=4, top_k=2, d_ff=128, M=300,
+                                       budgets=(2, 3, 4), bias_alpha=0.3),
     "s_f32_a": wl.small_config("s_f32_a", "f32", d=100, n_experts=12, top_k=3, d_ff=52, M=19, budgets=(3, 6, 12)),
     "tiny_f32": wl.CONFIGS["tiny_f32"],
 }
@@ -76,13 +82,17 @@ def test_layer_forward_parity_small(cases, name, policy):
         ref = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, B, policy)
         assert_routing_equal(taps, ref, B)
         assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)
+        # without taps the budget stage may skip the grouping of the pairs: same output, bit for bit
+        out_plain = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], B, policy, c["ws"])
+        torch.cuda.synchronize()
+        assert torch.equal(out_plain, out)
         if policy == mb.TRUNCATE:
             dropped = [t for t in range(cfg.M) if np.all(ref["tok_ids"][t] < 0)]
             if dropped:
                 assert torch.all(out[dropped] == 0), "tokens without a surviving expert must get exact zeros"
 
 
-@pytest.mark.parametrize("name", ["s_bf16_a", "s_f32_a"])
+@pytest.mark.parametrize("name", ["s_bf16_a", "s_bf16_self", "s_f32_a"])
 def test_stage_calls_compose_to_the_fused_call(cases, name):
     """route -> budget -> expert_ffn through their own entry points equals layer_forward bit for bit."""
     c = cases(name)

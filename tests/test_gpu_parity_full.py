@@ -61,6 +61,11 @@ def test_full_size_routing_and_sampled_outputs(full_case, policy):
         want = O.combine(c["h_o"], ref["tok_ids"], ref["tok_w"], Wexp["w_gate"], Wexp["w_up"], Wexp["w_down"],
                          tokens=sample)
         assert_out_close(got, want, cfg.dtype, rows=sample, what=f"{cfg.name} B={B} policy={policy}")
+        # the call the benchmark times: no taps, so the budget stage skips the grouping of the pairs
+        out_plain = torch.full_like(out, float("nan"))
+        mb.LayerForwardCall(c["desc"], c["W_d"], c["h_d"], B, policy, c["ws"], out_plain)()
+        torch.cuda.synchronize()
+        assert torch.equal(out_plain, out), "layer output differs between the call with and without taps"
         if policy == mb.TRUNCATE:
             dropped = [t for t in range(cfg.M) if np.all(ref["tok_ids"][t] < 0)]
             if dropped:
