@@ -22,9 +22,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
-# HBM traffic of one gate/up-pass launch at the default workload, from the rocprofv3 --pmc runs
-# summarised under profiles/ (None until measured for the current kernel).
-MEASURED_TRAFFIC_BYTES = None
+# HBM traffic (bytes fetched + written) of one gate/up-pass launch at the default workload (olmoe_m63, B=32,
+# substitution; mean over the six weight sets, 28.5 loaded experts), from the two rocprofv3 --pmc runs summarised
+# in profiles/gateup_olmoe_m63_B32_hbm_traffic.md: FETCH_SIZE 117914.9 x 2.0 (copy-kernel calibration) + WRITE_SIZE
+# 1008.0 KiB.  Reported only for that workload.
+MEASURED_TRAFFIC_BYTES = int((117914.9 * 2.0 + 1008.0) * 1024)
 
 
 def parse_args():
@@ -39,6 +41,9 @@ def parse_args():
     ap.add_argument("--sweep-steps", type=int, default=60)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="also run a plain 256 MiB device-to-device copy a few times: under rocprofv3 --pmc its "
+                         "FETCH_SIZE / WRITE_SIZE readings calibrate the counters against a known number of bytes")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="minimum host time spent in the CPU oracle (whole layers, one weight set after another)")
     return ap.parse_args()
@@ -88,6 +93,7 @@ def main():
     policy = mb.SUBSTITUTE if args.policy == "substitution" else mb.TRUNCATE
     desc = mb.LayerDesc(cfg.d, cfg.n_experts, cfg.top_k, cfg.d_ff, mb.BF16, cfg.renorm)
     M, B = cfg.M, args.budget
+    default_workload = (args.config, args.budget, args.policy, args.sets) == ("olmoe_m63", 32, "substitution", 6)
 
     gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
     bias = torch.from_numpy(wl.router_bias(cfg)).cuda()
@@ -105,6 +111,14 @@ def main():
             torch.cuda.synchronize()
             counts.append(int(n_loaded_t.item()))
         return sum(counts) / len(counts)
+
+    if args.copy_reference:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the timed region: K steps of the whole hot path, inputs resident in HBM -------------------
     calls = [mb.LayerForwardCall(desc, W, h, B, policy, ws, out) for W in sets]
@@ -152,7 +166,7 @@ def main():
                       "peak_GBps": HBM_PEAK_GBPS, "frac": round(layer_gbps / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "kernel": "expert FFN gate/up pass", "achieved": round(gateup_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(gateup_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_bytes_per_launch": gateup_bytes,
+                     "traffic": MEASURED_TRAFFIC_BYTES if default_workload else None, "algorithmic_bytes_per_launch": gateup_bytes,
                      "avg_launch_ms": round(stage_ms["gate_up"], 5), "down_pass_GBps": round(down_gbps, 1)},
         "stage_ms": {k_: round(v, 5) for k_, v in stage_ms.items()},
         "ms_per_step_traced": round(ms_traced, 5),
@@ -189,7 +203,7 @@ def main():
         pol = O.SUBSTITUTE if policy == mb.SUBSTITUTE else O.TRUNCATE
         hh = h.float().cpu().numpy()
         layers, spent = 0, 0.0
-        while spent < args.cpu_seconds and layers < 4 * len(sets):
+        while spent < args.cpu_seconds and layers < 64 * len(sets):
             W = sets[layers % len(sets)]
             Wh = {key: (val.float().cpu().numpy() if val.dtype == torch.bfloat16 else val.cpu().numpy())
                   for key, val in W.items()}
