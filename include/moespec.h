@@ -85,14 +85,17 @@ const char *moespec_status_string(int32_t status);
 
 /*
  * Checks that the kernels cover this layer shape: d and d_ff multiples of 32 (bf16) or 4 (f32),
- * 1 <= top_k <= n_experts <= 1024, top_k <= 64, dtype and renorm valid.
+ * d <= 8192, 1 <= top_k <= n_experts <= 1024, top_k <= 64, n_experts * d_ff * d < 2^40, dtype and
+ * renorm valid.
  * Returns MOESPEC_OK, MOESPEC_ERR_INVALID_ARG or MOESPEC_ERR_UNSUPPORTED_SHAPE.  Host only.
  */
 moespec_status moespec_check_desc(const moespec_desc *desc);
 
 /*
- * Bytes of workspace any call below needs for trees of up to M_max tokens (0 on an invalid
- * descriptor or M_max < 1).  Host only.
+ * Bytes of workspace any call below needs for trees of up to M_max tokens, 1 <= M_max <= 65535
+ * (0 on an invalid descriptor or M_max out of range).  The workspace is scratch: its content need
+ * not be initialised and is not preserved between calls; calls that share one workspace must not
+ * overlap in time.  Host only.
  */
 size_t moespec_workspace_bytes(const moespec_desc *desc, int32_t M_max);
 
@@ -158,7 +161,10 @@ moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weight
  * B = N is the unbudgeted layer of Eq. (2), which loads the expert union of Eq. (3).
  * The tap pointers (all optional, any may be NULL) receive copies of the intermediates with the
  * shapes documented above: probs [M,N], scores [N], budget_ids [B], tok_ids [M,k], tok_w [M,k],
- * seg_expert [B], seg_off [B+1], perm [M*k], n_loaded [1].
+ * seg_expert [B], seg_off [B+1], perm [M*k], n_loaded [1].  The grouping of the pairs into segments
+ * (seg_off, perm, n_loaded) is an extra serial step that small trees only pay when one of those three
+ * taps is given: without them the expert passes find their segments themselves.  The output is the
+ * same, bit for bit, either way.
  */
 #define MOESPEC_TRACE_POINTS 6
 typedef struct {
