@@ -20,6 +20,12 @@ Steps and the passages they follow
   expert                          SwiGLU feed-forward (the paper leaves E_i open;
                                   the workloads fix SwiGLU without biases)
   combine / layer_forward         Eq. (2), (7), (8); Algorithm 1
+  calibration_counts / static_shortlist
+                                  Eq. (4), "Static Ranking": selection frequency over
+                                  calibration tokens and the B most frequent experts
+  coverage_curve                  cumulative routing probability captured by the top-B
+                                  experts, B = 1..N (Section 4.6)
+  reconstruction_error            Section 4.5: ||O_S - O*||^2 / ||O*||^2, O* from Eq. (2)
   segments                        the per-expert grouping of surviving
                                   (token, slot) pairs; defined here, the paper's
                                   batched matmul (Appendix C) hides it
@@ -132,6 +138,50 @@ def coverage(scores, S: Sequence[int]) -> float:
     """Fraction of the tree's routing mass held by the shortlist."""
     s = _f64(scores)
     return float(sum(s[i] for i in S) / np.sum(s))
+
+
+def coverage_curve(scores) -> np.ndarray:
+    """curve[B-1] = share of the tree's routing probability held by the B highest-scoring experts,
+    B = 1..N (Section 4.6: cumulative routing probability captured by the top-B experts)."""
+    s = _f64(scores)
+    total = 0.0
+    for i in range(s.shape[0]):
+        total = total + s[i]
+    curve = np.zeros(s.shape[0], dtype=np.float64)
+    acc = 0.0
+    for r, i in enumerate(rank_desc(s)):
+        acc = acc + s[i]
+        curve[r] = acc / total
+    return curve
+
+
+# --------------------------------------------------------------------------- Eq. (4)
+def calibration_counts(topk_ids, n_experts: int, counts=None) -> np.ndarray:
+    """c_i = number of calibration tokens h with i in T_k(h); `counts` (int64) carries earlier batches."""
+    c = np.zeros(n_experts, dtype=np.int64) if counts is None else np.array(counts, dtype=np.int64)
+    for row in np.asarray(topk_ids):
+        for i in row:
+            if i >= 0:
+                c[int(i)] += 1
+    return c
+
+
+def static_shortlist(counts, B: int) -> List[int]:
+    """The B experts with the highest selection frequency, most frequent first (ties: lowest id)."""
+    c = [int(v) for v in counts]
+    return sorted(range(len(c)), key=lambda i: (-c[i], i))[:B]
+
+
+# --------------------------------------------------------------------------- Section 4.5
+def reconstruction_error(out_budgeted, out_full) -> float:
+    """||O_S - O*||^2 / ||O*||^2 over all tokens of the layer (squared Frobenius norms)."""
+    a, b = _f64(out_budgeted), _f64(out_full)
+    num = den = 0.0
+    for t in range(a.shape[0]):
+        diff = a[t] - b[t]
+        num = num + float(np.dot(diff, diff))
+        den = den + float(np.dot(b[t], b[t]))
+    return num / den
 
 
 # --------------------------------------------------------------------------- Eq. (7)
