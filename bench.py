@@ -176,13 +176,20 @@ def main():
     if not args.no_sweep:
         rows = []
         budgets = sorted(set(cfg.budgets) | {cfg.n_experts})
+        # quality proxies on the synthetic data (first weight set, outside the timed loops): share of the routing
+        # probability held by the top-B experts, and ||O_S - O*||^2 / ||O*||^2 against the B = N output
+        full, full_taps = mb.moespec_layer_forward(desc, sets[0], h, cfg.n_experts, policy, ws, taps=True)
+        curve = mb.moespec_coverage_curve(desc, full_taps["scores"]).cpu().tolist()
         for b in budgets:
             if policy == mb.SUBSTITUTE and b < cfg.top_k:
                 continue
             sc = [mb.LayerForwardCall(desc, W, h, b, policy, ws, out) for W in sets]
             ms = timed_steps(torch, sc, args.sweep_steps, 6)
             nl = loaded_experts(b)
-            rows.append({"B": b, "loaded_experts": nl, "ms_per_layer": round(ms, 5),
+            mb.LayerForwardCall(desc, sets[0], h, b, policy, ws, out)()
+            rec = float(mb.moespec_reconstruction_error(desc, out, full, ws)[0].item())
+            rows.append({"B": b, "loaded_experts": nl, "coverage": round(curve[b - 1], 4),
+                         "reconstruction_error": round(rec, 5), "ms_per_layer": round(ms, 5),
                          "tokens_per_s": round(M / (ms * 1e-3), 1),
                          "GBps": round(nl * cfg.expert_bytes / (ms * 1e-3) / 1e9, 1),
                          "frac_of_peak": round(nl * cfg.expert_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})

@@ -13,6 +13,10 @@
  *                          and the weighted combine
  *   moespec_layer_forward  all of the above in one call (Algorithm 1)
  *
+ * and, around that path, the static ranking of Eq. (4) (moespec_calibration_count,
+ * moespec_static_shortlist: a shortlist fixed from calibration data, passed in as ext_shortlist)
+ * and two analysis quantities of Section 4 (moespec_coverage_curve, moespec_reconstruction_error).
+ *
  * Conventions (all calls)
  *   Pointers  Every buffer pointer is a DEVICE pointer unless it is a descriptor struct
  *             (moespec_desc, moespec_weights are read on the host).  All tensors are row-major,
@@ -190,6 +194,43 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
                                      const void *residual, void *out,
                                      const moespec_taps *taps,
                                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Static ranking - Eq. (4): c_i = number of calibration tokens h with i in T_k(h).
+ *   topk_ids [M, k] int32  in     natural top-k ids of a batch of calibration tokens (moespec_route);
+ *                                 entries outside [0, N) are ignored
+ *   counts   [N] int64     in/out selection frequencies, incremented in place (zero them before the
+ *                                 first batch; later batches accumulate)
+ * Device pointers; asynchronous on hip_stream; no workspace.
+ */
+moespec_status moespec_calibration_count(const moespec_desc *desc, const int32_t *topk_ids, int32_t M,
+                                         int64_t *counts, void *hip_stream);
+
+/*
+ * Static ranking - Eq. (4) and the sentence after it: the B experts with the highest c_i, most
+ * frequent first, ties to the lowest id.  The result is what moespec_budget / moespec_layer_forward
+ * take as ext_shortlist.
+ *   counts [N] int64 in, shortlist [B] int32 out (device), 1 <= B <= N.
+ */
+moespec_status moespec_static_shortlist(const moespec_desc *desc, const int64_t *counts, int32_t B,
+                                        int32_t *shortlist, void *hip_stream);
+
+/*
+ * Coverage analysis - Section 4.6: curve[B-1] = share of the tree's routing probability captured by
+ * the B highest-scoring experts, B = 1..N, from the aggregate scores of Eq. (5).
+ *   scores [N] double in (the scores tap), curve [N] double out (device).
+ */
+moespec_status moespec_coverage_curve(const moespec_desc *desc, const double *scores, double *curve,
+                                      void *hip_stream);
+
+/*
+ * Reconstruction error - Section 4.5: ||O_S - O*||^2 / ||O*||^2 over all M tokens, O_S the budgeted
+ * layer output and O* the full output of Eq. (2) (a layer call with B = N), accumulated in fp64.
+ *   out_budgeted, out_full [M, d] dtype in;  err [3] double out: ratio, numerator, denominator.
+ * Uses the workspace as scratch (same size rule as the other calls).
+ */
+moespec_status moespec_reconstruction_error(const moespec_desc *desc, const void *out_budgeted, const void *out_full,
+                                            int32_t M, double *err, void *ws, size_t ws_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

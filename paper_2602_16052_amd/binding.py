@@ -23,7 +23,9 @@ F32, BF16 = 0, 1
 TRUNCATE, SUBSTITUTE = 0, 1
 
 EXPORTS = ("moespec_abi_version", "moespec_status_string", "moespec_check_desc", "moespec_workspace_bytes",
-           "moespec_route", "moespec_budget", "moespec_expert_ffn", "moespec_layer_forward")
+           "moespec_route", "moespec_budget", "moespec_expert_ffn", "moespec_layer_forward",
+           "moespec_calibration_count", "moespec_static_shortlist", "moespec_coverage_curve",
+           "moespec_reconstruction_error")
 
 
 class MoeSpecError(RuntimeError):
@@ -87,6 +89,15 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moespec_layer_forward.restype = c_int32
     lib.moespec_layer_forward.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_int32,
                                           c_void_p, c_void_p, c_void_p, POINTER(Taps), c_void_p, c_size_t, c_void_p]
+    lib.moespec_calibration_count.restype = c_int32
+    lib.moespec_calibration_count.argtypes = [POINTER(Desc), c_void_p, c_int32, c_void_p, c_void_p]
+    lib.moespec_static_shortlist.restype = c_int32
+    lib.moespec_static_shortlist.argtypes = [POINTER(Desc), c_void_p, c_int32, c_void_p, c_void_p]
+    lib.moespec_coverage_curve.restype = c_int32
+    lib.moespec_coverage_curve.argtypes = [POINTER(Desc), c_void_p, c_void_p, c_void_p]
+    lib.moespec_reconstruction_error.restype = c_int32
+    lib.moespec_reconstruction_error.argtypes = [POINTER(Desc), c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
+                                                 c_size_t, c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -329,3 +340,47 @@ def moespec_layer_forward(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: 
         _stream(stream))
     _check(st, "moespec_layer_forward")
     return (out, tap_t) if taps else out
+
+
+def moespec_calibration_count(desc: LayerDesc, topk_ids: torch.Tensor, counts: torch.Tensor, stream=None) -> torch.Tensor:
+    """Eq. (4): counts[i] += number of rows of topk_ids [M, k] that contain expert i.  Returns counts."""
+    M = topk_ids.shape[0]
+    cd = desc.c()
+    st = load_library().moespec_calibration_count(
+        ctypes.byref(cd), _ptr(topk_ids, torch.int32, M * desc.top_k, "topk_ids"), M,
+        _ptr(counts, torch.int64, desc.n_experts, "counts"), _stream(stream))
+    _check(st, "moespec_calibration_count")
+    return counts
+
+
+def moespec_static_shortlist(desc: LayerDesc, counts: torch.Tensor, B: int, stream=None) -> torch.Tensor:
+    """The B most frequently selected experts (Eq. (4)), most frequent first; int32 [B], usable as ext_shortlist."""
+    out = torch.empty(max(int(B), 1), dtype=torch.int32, device=counts.device)
+    cd = desc.c()
+    st = load_library().moespec_static_shortlist(ctypes.byref(cd), _ptr(counts, torch.int64, desc.n_experts, "counts"),
+                                                 int(B), _ptr(out), _stream(stream))
+    _check(st, "moespec_static_shortlist")
+    return out
+
+
+def moespec_coverage_curve(desc: LayerDesc, scores: torch.Tensor, stream=None) -> torch.Tensor:
+    """Section 4.6: share of the routing probability captured by the top-B experts, B = 1..N; float64 [N]."""
+    out = torch.empty(desc.n_experts, dtype=torch.float64, device=scores.device)
+    cd = desc.c()
+    st = load_library().moespec_coverage_curve(ctypes.byref(cd), _ptr(scores, torch.float64, desc.n_experts, "scores"),
+                                               _ptr(out), _stream(stream))
+    _check(st, "moespec_coverage_curve")
+    return out
+
+
+def moespec_reconstruction_error(desc: LayerDesc, out_budgeted: torch.Tensor, out_full: torch.Tensor,
+                                 ws: torch.Tensor, stream=None) -> torch.Tensor:
+    """Section 4.5: float64 [3] = (||O_S - O*||^2 / ||O*||^2, numerator, denominator)."""
+    M, dt = out_full.shape[0], desc.torch_dtype
+    err = torch.empty(3, dtype=torch.float64, device=out_full.device)
+    cd = desc.c()
+    st = load_library().moespec_reconstruction_error(
+        ctypes.byref(cd), _ptr(out_budgeted, dt, M * desc.d, "out_budgeted"), _ptr(out_full, dt, M * desc.d, "out_full"),
+        M, _ptr(err), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "moespec_reconstruction_error")
+    return err

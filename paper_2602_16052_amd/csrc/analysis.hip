@@ -1,0 +1,137 @@
+// Analysis steps around the hot path: the static ranking of Eq. (4) (selection frequency over
+// calibration tokens and the B most frequent experts, which enter the layer as an external
+// shortlist), the coverage curve of Section 4.6 (cumulative routing probability captured by the
+// top-B experts) and the reconstruction error of Section 4.5 (||O_S - O*||^2 / ||O*||^2).
+// Tiny, latency-bound kernels; integer work is exact, floating point is fp64 in a fixed order.
+#include "common.h"
+
+namespace moespec {
+
+constexpr int kAnalysisThreads = 1024;
+
+// c_i += #{(t, slot) : topk_ids[t, slot] == i}.  Integer atomics: the result does not depend on order.
+__global__ __launch_bounds__(256) void calibration_count_kernel(const int32_t *__restrict__ topk_ids, int n, int N,
+                                                                unsigned long long *__restrict__ counts) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const int e = topk_ids[i];
+    if ((uint32_t)e < (uint32_t)N) atomicAdd(&counts[e], 1ull);
+  }
+}
+
+// shortlist[r] = expert with rank r < B when ordered by (count descending, id ascending).  One workgroup.
+__global__ __launch_bounds__(kAnalysisThreads) void static_shortlist_kernel(const long long *__restrict__ counts,
+                                                                            int N, int B,
+                                                                            int32_t *__restrict__ shortlist) {
+  __shared__ long long c[1024];
+  for (int i = threadIdx.x; i < N; i += blockDim.x) c[i] = counts[i];
+  __syncthreads();
+  for (int i = threadIdx.x; i < N; i += blockDim.x) {
+    const long long ci = c[i];
+    int r = 0;
+    for (int j = 0; j < N; ++j) r += (c[j] > ci || (c[j] == ci && j < i)) ? 1 : 0;
+    if (r < B) shortlist[r] = i;
+  }
+}
+
+// curve[B-1] = (sum of the B largest scores) / (sum of all scores); the total is added in expert order,
+// the partial sums in rank order (ties: lowest id first).  One workgroup.
+__global__ __launch_bounds__(kAnalysisThreads) void coverage_curve_kernel(const double *__restrict__ scores, int N,
+                                                                          double *__restrict__ curve) {
+  __shared__ double s[1024];
+  __shared__ int32_t order[1024];
+  for (int i = threadIdx.x; i < N; i += blockDim.x) s[i] = scores[i];
+  __syncthreads();
+  for (int i = threadIdx.x; i < N; i += blockDim.x) {
+    const double si = s[i];
+    int r = 0;
+    for (int j = 0; j < N; ++j) r += ranks_before(s[j], j, si, i) ? 1 : 0;
+    order[r] = i;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double total = 0.0;
+    for (int i = 0; i < N; ++i) total += s[i];
+    double acc = 0.0;
+    for (int r = 0; r < N; ++r) {
+      acc += s[order[r]];
+      curve[r] = acc / total;
+    }
+  }
+}
+
+// part[2 t] = ||a_t - b_t||^2, part[2 t + 1] = ||b_t||^2 for token t (one workgroup per token; thread i
+// folds the elements i, i + 256, ... in ascending order, then the 256 partial sums are folded in
+// thread order).
+template <typename T>
+__global__ __launch_bounds__(256) void sqdiff_rows_kernel(const T *__restrict__ a, const T *__restrict__ b, int d,
+                                                          double *__restrict__ part) {
+  __shared__ double num[256], den[256];
+  const int t = blockIdx.x, tid = threadIdx.x;
+  double n = 0.0, q = 0.0;
+  for (int j = tid; j < d; j += 256) {
+    const double av = (double)Elem<T>::load(a + (size_t)t * d + j), bv = (double)Elem<T>::load(b + (size_t)t * d + j);
+    const double df = av - bv;
+    n += df * df;
+    q += bv * bv;
+  }
+  num[tid] = n;
+  den[tid] = q;
+  __syncthreads();
+  if (tid == 0) {
+    double sn = 0.0, sd = 0.0;
+    for (int i = 0; i < 256; ++i) {
+      sn += num[i];
+      sd += den[i];
+    }
+    part[2 * t] = sn;
+    part[2 * t + 1] = sd;
+  }
+}
+
+// err[0] = num / den, err[1] = num, err[2] = den, tokens added in ascending order.
+__global__ void sqdiff_total_kernel(const double *__restrict__ part, int M, double *__restrict__ err) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double sn = 0.0, sd = 0.0;
+  for (int t = 0; t < M; ++t) {
+    sn += part[2 * t];
+    sd += part[2 * t + 1];
+  }
+  err[0] = sn / sd;
+  err[1] = sn;
+  err[2] = sd;
+}
+
+hipError_t launch_calibration_count(const int32_t *topk_ids, int M, int k, int N, int64_t *counts, hipStream_t st) {
+  const int n = M * k;
+  int blocks = (n + 255) / 256;
+  blocks = blocks > 1024 ? 1024 : blocks;
+  calibration_count_kernel<<<blocks, 256, 0, st>>>(topk_ids, n, N, reinterpret_cast<unsigned long long *>(counts));
+  return hipGetLastError();
+}
+
+hipError_t launch_static_shortlist(const int64_t *counts, int N, int B, int32_t *shortlist, hipStream_t st) {
+  static_shortlist_kernel<<<1, kAnalysisThreads, 0, st>>>(reinterpret_cast<const long long *>(counts), N, B,
+                                                          shortlist);
+  return hipGetLastError();
+}
+
+hipError_t launch_coverage_curve(const double *scores, int N, double *curve, hipStream_t st) {
+  coverage_curve_kernel<<<1, kAnalysisThreads, 0, st>>>(scores, N, curve);
+  return hipGetLastError();
+}
+
+hipError_t launch_reconstruction_error(const moespec_desc &ds, const void *out_budgeted, const void *out_full, int M,
+                                       double *part, double *err, hipStream_t st) {
+  if (ds.dtype == MOESPEC_BF16)
+    sqdiff_rows_kernel<uint16_t><<<M, 256, 0, st>>>(static_cast<const uint16_t *>(out_budgeted),
+                                                    static_cast<const uint16_t *>(out_full), ds.d, part);
+  else
+    sqdiff_rows_kernel<float><<<M, 256, 0, st>>>(static_cast<const float *>(out_budgeted),
+                                                 static_cast<const float *>(out_full), ds.d, part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  sqdiff_total_kernel<<<1, 64, 0, st>>>(part, M, err);
+  return hipGetLastError();
+}
+
+}  // namespace moespec

@@ -163,4 +163,40 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
   return from_hip(e);
 }
 
+moespec_status moespec_calibration_count(const moespec_desc *desc, const int32_t *topk_ids, int32_t M,
+                                         int64_t *counts, void *hip_stream) {
+  moespec_status s = check_desc(desc);
+  if (s != MOESPEC_OK) return s;
+  if (M < 1 || M > kMaxTokens || !topk_ids || !counts) return MOESPEC_ERR_INVALID_ARG;
+  return from_hip(launch_calibration_count(topk_ids, M, desc->top_k, desc->n_experts, counts,
+                                           static_cast<hipStream_t>(hip_stream)));
+}
+
+moespec_status moespec_static_shortlist(const moespec_desc *desc, const int64_t *counts, int32_t B,
+                                        int32_t *shortlist, void *hip_stream) {
+  moespec_status s = check_desc(desc);
+  if (s != MOESPEC_OK) return s;
+  if (B < 1 || B > desc->n_experts || !counts || !shortlist) return MOESPEC_ERR_INVALID_ARG;
+  return from_hip(launch_static_shortlist(counts, desc->n_experts, B, shortlist, static_cast<hipStream_t>(hip_stream)));
+}
+
+moespec_status moespec_coverage_curve(const moespec_desc *desc, const double *scores, double *curve,
+                                      void *hip_stream) {
+  moespec_status s = check_desc(desc);
+  if (s != MOESPEC_OK) return s;
+  if (!scores || !curve) return MOESPEC_ERR_INVALID_ARG;
+  return from_hip(launch_coverage_curve(scores, desc->n_experts, curve, static_cast<hipStream_t>(hip_stream)));
+}
+
+moespec_status moespec_reconstruction_error(const moespec_desc *desc, const void *out_budgeted, const void *out_full,
+                                            int32_t M, double *err, void *ws, size_t ws_bytes, void *hip_stream) {
+  moespec_status s = check_common(desc, M, ws, ws_bytes);
+  if (s != MOESPEC_OK) return s;
+  if (!out_budgeted || !out_full || !err) return MOESPEC_ERR_INVALID_ARG;
+  Workspace w = carve_workspace(*desc, M, ws);
+  // the per-token partial sums (2 M doubles) borrow the y buffer (M * k * d floats, d >= 4)
+  return from_hip(launch_reconstruction_error(*desc, out_budgeted, out_full, M, reinterpret_cast<double *>(w.y), err,
+                                              static_cast<hipStream_t>(hip_stream)));
+}
+
 }  // extern "C"

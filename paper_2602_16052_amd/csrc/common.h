@@ -180,5 +180,11 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                              float *y, int4 *items, bool items_ready, const int32_t *rank_count,
                              const int32_t *shortlist, hipStream_t st, void *const *trace = nullptr);
 bool expert_ffn_self_segmenting(const moespec_desc &ds, int M);
+// Analysis kernels (analysis.hip).  part: 2 M doubles of scratch.
+hipError_t launch_calibration_count(const int32_t *topk_ids, int M, int k, int N, int64_t *counts, hipStream_t st);
+hipError_t launch_static_shortlist(const int64_t *counts, int N, int B, int32_t *shortlist, hipStream_t st);
+hipError_t launch_coverage_curve(const double *scores, int N, double *curve, hipStream_t st);
+hipError_t launch_reconstruction_error(const moespec_desc &ds, const void *out_budgeted, const void *out_full, int M,
+                                       double *part, double *err, hipStream_t st);
 
 }  // namespace moespec

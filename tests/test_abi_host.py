@@ -122,6 +122,25 @@ def test_stage_calls_reject_bad_arguments(lib):
                                   wsb, None) == mb.ERR_INVALID_ARG
 
 
+def test_analysis_calls_reject_bad_arguments(lib):
+    d = D()
+    cd = d.c()
+    wsb = mb.workspace_bytes(d, 8)
+    P = 0x50000
+    assert lib.moespec_calibration_count(ctypes.byref(cd), None, 8, P, None) == mb.ERR_INVALID_ARG
+    assert lib.moespec_calibration_count(ctypes.byref(cd), P, 0, P, None) == mb.ERR_INVALID_ARG
+    assert lib.moespec_calibration_count(ctypes.byref(cd), P, 8, None, None) == mb.ERR_INVALID_ARG
+    assert lib.moespec_static_shortlist(ctypes.byref(cd), P, 0, P, None) == mb.ERR_INVALID_ARG
+    assert lib.moespec_static_shortlist(ctypes.byref(cd), P, d.n_experts + 1, P, None) == mb.ERR_INVALID_ARG
+    assert lib.moespec_static_shortlist(ctypes.byref(cd), None, 4, P, None) == mb.ERR_INVALID_ARG
+    assert lib.moespec_coverage_curve(ctypes.byref(cd), None, P, None) == mb.ERR_INVALID_ARG
+    assert lib.moespec_coverage_curve(ctypes.byref(cd), P, None, None) == mb.ERR_INVALID_ARG
+    assert lib.moespec_reconstruction_error(ctypes.byref(cd), P, None, 8, P, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    assert lib.moespec_reconstruction_error(ctypes.byref(cd), P, P, 8, P, 0x10000, 16,
+                                            None) == mb.ERR_WORKSPACE_TOO_SMALL
+    assert lib.moespec_reconstruction_error(ctypes.byref(cd), P, P, 8, None, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     d = D()

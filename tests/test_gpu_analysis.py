@@ -1,0 +1,109 @@
+"""GPU parity of the steps around the hot path: static ranking (Eq. (4)) feeding the layer as an external
+shortlist, the coverage curve (Section 4.6) and the reconstruction error (Section 4.5)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moespec_oracle as O
+from paper_2602_16052_amd import binding as mb
+from paper_2602_16052_amd import workloads as wl
+
+from gpu_common import (assert_out_close, assert_routing_equal, desc_of, oracle_weights, out_to_numpy, to_device,
+                        upload_weights)
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    "an_bf16": wl.small_config("an_bf16", "bf16", d=256, n_experts=24, top_k=4, d_ff=128, M=41, budgets=(6, 12, 24),
+                               bias_alpha=1.0),
+    "an_f32": wl.small_config("an_f32", "f32", d=64, n_experts=10, top_k=2, d_ff=40, M=17, budgets=(2, 5, 10),
+                              bias_alpha=0.3),
+}
+
+
+@pytest.fixture(scope="module", params=list(CASES))
+def case(request):
+    cfg = CASES[request.param]
+    h, W = wl.hidden_states(cfg), wl.layer_weights(cfg)
+    desc = desc_of(cfg)
+    return dict(cfg=cfg, desc=desc, W=W, W_d=upload_weights(W), W_o=oracle_weights(W), h_d=to_device(h),
+                h_o=wl.as_f32(h), ws=mb.alloc_workspace(desc, 64))
+
+
+def test_static_ranking_counts_shortlist_and_layer(case):
+    """Calibration batches (different seeds, ragged sizes) -> c_i -> static shortlist -> budgeted layer."""
+    c = case
+    cfg, desc = c["cfg"], c["desc"]
+    counts_d = torch.zeros(cfg.n_experts, dtype=torch.int64, device="cuda")
+    counts_o = None
+    for seed, M in ((11, 64), (12, 1), (13, 37)):
+        hb = wl.hidden_states(cfg, M=M, seed=seed)
+        r = mb.moespec_route(desc, c["W_d"], to_device(hb), c["ws"])
+        mb.moespec_calibration_count(desc, r["topk_ids"], counts_d)
+        _, ids, _ = O.route(wl.as_f32(hb), c["W_o"]["w_router"], c["W_o"]["b_router"], cfg.top_k, cfg.renorm)
+        counts_o = O.calibration_counts(ids, cfg.n_experts, counts_o)
+    torch.cuda.synchronize()
+    assert np.array_equal(counts_d.cpu().numpy(), counts_o)
+    assert int(counts_o.sum()) == (64 + 1 + 37) * cfg.top_k
+    for B in cfg.budgets:
+        S_d = mb.moespec_static_shortlist(desc, counts_d, B)
+        torch.cuda.synchronize()
+        S_o = O.static_shortlist(counts_o, B)
+        assert S_d.cpu().tolist() == S_o
+        for policy in (mb.TRUNCATE, mb.SUBSTITUTE):
+            if policy == mb.SUBSTITUTE and B < cfg.top_k:
+                continue
+            out, taps = mb.moespec_layer_forward(desc, c["W_d"], c["h_d"], B, policy, c["ws"], ext_shortlist=S_d,
+                                                 taps=True)
+            torch.cuda.synchronize()
+            ref = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, B, policy, ext_shortlist=S_o)
+            assert_routing_equal(taps, ref, B)
+            assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)
+
+
+def test_static_shortlist_ties_and_out_of_range_ids(case):
+    desc, N = case["desc"], case["cfg"].n_experts
+    counts = torch.tensor([7 if i % 3 == 0 else 2 for i in range(N)], dtype=torch.int64, device="cuda")
+    for B in (1, 4, N):
+        got = mb.moespec_static_shortlist(desc, counts, B).cpu().tolist()
+        assert got == O.static_shortlist(counts.cpu().numpy(), B)
+    # ids outside [0, N) (dropped slots of a restricted table) are not counted
+    ids = torch.tensor([[0, -1], [N, 3], [3, 3]], dtype=torch.int32, device="cuda")
+    d2 = mb.LayerDesc(desc.d, desc.n_experts, 2, desc.d_ff, desc.dtype, desc.renorm)
+    c = mb.moespec_calibration_count(d2, ids, torch.zeros(N, dtype=torch.int64, device="cuda"))
+    want = np.zeros(N, dtype=np.int64)
+    want[0], want[3] = 1, 3
+    assert np.array_equal(c.cpu().numpy(), want)
+
+
+def test_coverage_curve_and_reconstruction_error(case):
+    c = case
+    cfg, desc = c["cfg"], c["desc"]
+    full, taps = mb.moespec_layer_forward(desc, c["W_d"], c["h_d"], cfg.n_experts, mb.SUBSTITUTE, c["ws"], taps=True)
+    curve = mb.moespec_coverage_curve(desc, taps["scores"])
+    torch.cuda.synchronize()
+    ref = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, cfg.n_experts, O.SUBSTITUTE)
+    np.testing.assert_allclose(curve.cpu().numpy(), O.coverage_curve(ref["scores"]), rtol=1e-12)
+    # same input bits on both sides: the diagnostic itself is compared to 1e-12
+    np.testing.assert_allclose(curve.cpu().numpy(), O.coverage_curve(taps["scores"].cpu().numpy()), rtol=1e-14)
+    full_np = out_to_numpy(full)
+    errs = []
+    for B in cfg.budgets:
+        for policy in (mb.TRUNCATE, mb.SUBSTITUTE):
+            if policy == mb.SUBSTITUTE and B < cfg.top_k:
+                continue
+            out = mb.moespec_layer_forward(desc, c["W_d"], c["h_d"], B, policy, c["ws"])
+            err = mb.moespec_reconstruction_error(desc, out, full, c["ws"])
+            torch.cuda.synchronize()
+            e = err.cpu().numpy()
+            want = O.reconstruction_error(out_to_numpy(out), full_np)
+            assert e[0] == pytest.approx(want, rel=1e-12, abs=1e-300)
+            assert e[0] == pytest.approx(e[1] / e[2], rel=1e-15, abs=1e-300)
+            if B == cfg.n_experts:
+                assert e[0] == 0.0
+            # against the oracle's own layer outputs the error agrees to the output tolerance
+            ref_b = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, B, policy)
+            want_o = O.reconstruction_error(ref_b["out"], ref["out"])
+            assert abs(e[0] - want_o) <= 0.05 * max(want_o, 1e-3)
+            errs.append(e[0])
+    assert max(errs) > 0
