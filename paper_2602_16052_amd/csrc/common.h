@@ -107,6 +107,8 @@ __device__ inline void mixing_weights(const double *g, const int32_t *sel, int k
     w[s] = sel[s] < 0 ? 0.0 : (renorm ? g[sel[s]] / *denom : g[sel[s]]);
 }
 
+constexpr int kMaxDownSplits = 4;  // K-split copies of the per-pair outputs y
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Workspace carve-up shared by all entry points (host).
@@ -123,7 +125,7 @@ struct Workspace {
   int32_t *n_loaded;  // [1]
   int32_t *done;      // [1 + N] ticket counter of the budget stage, then surviving pairs per shortlist rank
   void *act;          // [M * k, F] dtype
-  float *y;           // [M * k, d]
+  float *y;           // [kMaxDownSplits][M * k, d]
   size_t bytes;
 };
 
@@ -150,7 +152,7 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
   w.n_loaded = static_cast<int32_t *>(take(sizeof(int32_t)));
   w.done = static_cast<int32_t *>(take(sizeof(int32_t) * (1 + N)));
   w.act = take(es * M * k * F);
-  w.y = static_cast<float *>(take(sizeof(float) * M * k * d));
+  w.y = static_cast<float *>(take(sizeof(float) * kMaxDownSplits * M * k * d));
   w.bytes = off;
   return w;
 }

@@ -30,6 +30,9 @@ SMALL = {
                                    budgets=(4, 9, 16), bias_alpha=0.8),
     "s_bf16_self_big": wl.small_config("s_bf16_self_big", "bf16", d=128, n_experts=4, top_k=2, d_ff=128, M=300,
                                        budgets=(2, 3, 4), bias_alpha=0.3),
+    # long F with few row tiles: the down pass is cut along F into partial sums that the combine adds up
+    "s_bf16_split": wl.small_config("s_bf16_split", "bf16", d=128, n_experts=4, top_k=2, d_ff=4096, M=20,
+                                    budgets=(2, 4), bias_alpha=0.5),
     "s_f32_a": wl.small_config("s_f32_a", "f32", d=100, n_experts=12, top_k=3, d_ff=52, M=19, budgets=(3, 6, 12)),
     "tiny_f32": wl.CONFIGS["tiny_f32"],
 }
