@@ -33,6 +33,13 @@ SMALL = {
     # long F with few row tiles: the down pass is cut along F into partial sums that the combine adds up
     "s_bf16_split": wl.small_config("s_bf16_split", "bf16", d=128, n_experts=4, top_k=2, d_ff=4096, M=20,
                                     budgets=(2, 4), bias_alpha=0.5),
+    # a tree beyond every small-tree limit: segments read from perm, routing table not staged in LDS
+    # (M k > 8192), several 128-pair rounds per segment
+    "s_bf16_m5000": wl.small_config("s_bf16_m5000", "bf16", d=128, n_experts=6, top_k=2, d_ff=128, M=5000,
+                                    budgets=(2, 4, 6), bias_alpha=0.4),
+    # the largest expert count and top-k the descriptor check admits
+    "s_bf16_n1024": wl.small_config("s_bf16_n1024", "bf16", d=64, n_experts=1024, top_k=64, d_ff=32, M=9,
+                                    budgets=(64, 300, 1024), bias_alpha=0.7),
     "s_f32_a": wl.small_config("s_f32_a", "f32", d=100, n_experts=12, top_k=3, d_ff=52, M=19, budgets=(3, 6, 12)),
     "tiny_f32": wl.CONFIGS["tiny_f32"],
 }
