@@ -25,6 +25,8 @@ Steps and the passages they follow
                                   calibration tokens and the B most frequent experts
   coverage_curve                  cumulative routing probability captured by the top-B
                                   experts, B = 1..N (Section 4.6)
+  oracle_ranking                  Eq. (6), "Oracle Ranking": greedy selection that minimises the
+                                  reconstruction error against the gold output O*
   reconstruction_error            Section 4.5: ||O_S - O*||^2 / ||O*||^2, O* from Eq. (2)
   segments                        the per-expert grouping of surviving
                                   (token, slot) pairs; defined here, the paper's
@@ -36,7 +38,10 @@ Readings where the paper is silent
   * a router bias ``b`` is added to the projection when given (the workloads use
     one to make routing heavy-tailed); ``b=None`` is Eq. (1) as printed;
   * substitution weights are the full-softmax g_i restricted to the new set,
-    renormalised over that set when the architecture renormalises.
+    renormalised over that set when the architecture renormalises;
+  * Eq. (6) writes the partial sum over all j in S + {i} with raw g; it is read as the sum over
+    (S + {i}) intersected with T_k(h_t) with the mixing weights of Eq. (2), so that the full set
+    reproduces the gold output O* exactly (an expert outside a token's top-k contributes nothing).
 
 Every function is pinned by tests/test_oracle_*.py against closed forms,
 brute force on tiny inputs, invariants the paper states and library routines.
@@ -170,6 +175,51 @@ def static_shortlist(counts, B: int) -> List[int]:
     """The B experts with the highest selection frequency, most frequent first (ties: lowest id)."""
     c = [int(v) for v in counts]
     return sorted(range(len(c)), key=lambda i: (-c[i], i))[:B]
+
+
+# --------------------------------------------------------------------------- Eq. (6)
+def expert_contributions(h, topk_ids, topk_w, w_gate, w_up, w_down, n_experts: int) -> np.ndarray:
+    """C[i, t, :] = g-bar_i(h_t) * E_i(h_t) if i is in T_k(h_t), else 0; the gold output is O* = sum_i C[i]."""
+    h = _f64(h)
+    bank = _ExpertBank(w_gate, w_up, w_down)
+    C = np.zeros((n_experts, h.shape[0], h.shape[1]), dtype=np.float64)
+    for t in range(h.shape[0]):
+        for j in range(np.asarray(topk_ids).shape[1]):
+            i = int(topk_ids[t][j])
+            if i >= 0:
+                C[i, t] = float(topk_w[t][j]) * expert(h[t], *bank.get(i))
+    return C
+
+
+def oracle_ranking(C, B: int):
+    """Greedy oracle of Eq. (6) on the per-expert contributions C[N, M, d].
+
+    Starting from the empty set, B times add the expert i outside S that minimises
+    sum_t ||O*_t - sum_{j in S + {i}} C[j, t]||^2 (ties: lowest id).  Returns the experts in the order
+    they were added and, after each addition, that error divided by ||O*||^2.
+    """
+    C = _f64(C)
+    N = C.shape[0]
+    gold = np.zeros(C.shape[1:], dtype=np.float64)
+    for i in range(N):
+        gold = gold + C[i]
+    denom = float(np.sum(gold * gold))
+    partial = np.zeros_like(gold)
+    S: List[int] = []
+    errs: List[float] = []
+    for _ in range(B):
+        best, best_err = -1, 0.0
+        for i in range(N):
+            if i in S:
+                continue
+            r = gold - (partial + C[i])
+            e = float(np.sum(r * r))
+            if best < 0 or e < best_err:
+                best, best_err = i, e
+        S.append(best)
+        partial = partial + C[best]
+        errs.append(best_err / denom)
+    return S, np.asarray(errs, dtype=np.float64)
 
 
 # --------------------------------------------------------------------------- Section 4.5

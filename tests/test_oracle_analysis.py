@@ -95,3 +95,93 @@ def test_reconstruction_error_of_the_budgeted_layer_falls_to_zero_at_full_budget
     full = O.unbudgeted_forward(h, W, k, True)
     errs = [O.reconstruction_error(O.layer_forward(h, W, k, True, B, O.SUBSTITUTE)["out"], full) for B in (2, 4, 6)]
     assert errs[-1] == 0.0 and errs[0] > 0.0
+
+
+# ------------------------------------------------------------------------------------- Eq. (6)
+def _random_contributions(rng, N, M, d, k):
+    """Contributions with the structure of a routed layer: every token has exactly k non-zero experts."""
+    C = np.zeros((N, M, d))
+    for t in range(M):
+        for i in rng.permutation(N)[:k]:
+            C[i, t] = rng.standard_normal(d) * rng.uniform(0.1, 2.0)
+    return C
+
+
+def test_oracle_ranking_orthogonal_contributions_are_picked_by_energy():
+    """Experts that write to disjoint coordinates: adding expert i lowers the error by ||C_i||^2 exactly,
+    so the greedy order is descending energy and the error curve is the closed form."""
+    rng = np.random.default_rng(0)
+    N, M = 5, 7
+    C = np.zeros((N, M, N * 3))
+    for i in range(N):
+        C[i, :, 3 * i:3 * i + 3] = rng.standard_normal((M, 3)) * (i + 1) * (1 if i != 2 else 3.5)
+    energy = np.array([np.sum(C[i] ** 2) for i in range(N)])
+    S, errs = O.oracle_ranking(C, N)
+    assert S == list(np.argsort(-energy, kind="stable"))
+    want = 1.0 - np.cumsum(energy[S]) / energy.sum()
+    np.testing.assert_allclose(errs, want, atol=1e-14)
+
+
+def test_oracle_ranking_each_step_is_the_brute_force_minimiser():
+    rng = np.random.default_rng(4)
+    N, M, d, k = 7, 9, 6, 3
+    C = _random_contributions(rng, N, M, d, k)
+    gold = C.sum(axis=0)
+    S, errs = O.oracle_ranking(C, N)
+    assert sorted(S) == list(range(N)) and errs[-1] == pytest.approx(0.0, abs=1e-28)
+    assert np.all(np.diff(errs) <= 1e-15)          # adding the best expert never increases the error
+    for step in range(N):
+        chosen = S[:step]
+        cand = {i: np.sum((gold - C[chosen + [i]].sum(axis=0)) ** 2) for i in range(N) if i not in chosen}
+        best = min(cand, key=lambda i: (cand[i], i))
+        assert best == S[step]
+        assert errs[step] == pytest.approx(cand[best] / np.sum(gold ** 2), rel=1e-12)
+
+
+def test_oracle_ranking_prefers_complementary_over_correlated_experts():
+    """Two experts with the same large contribution direction: after taking one, the other's marginal gain
+    collapses and a smaller but independent expert is taken first (Section 4.5's explanation of the gap)."""
+    u, v = np.array([1.0, 0.0, 0.0]), np.array([0.0, 1.0, 0.0])
+    C = np.zeros((3, 1, 3))
+    C[0, 0], C[1, 0], C[2, 0] = 3.0 * u, 2.9 * u - 0.0 * v, 1.0 * v
+    # gold = 5.9 u + v; single-expert errors: e0 = 2.9^2 + 1, e1 = 3^2 + 1, e2 = 5.9^2  -> pick 0
+    # then: {0,1}: 1 ; {0,2}: 2.9^2 -> pick 1 (here the correlated expert still helps: same sign)
+    S, errs = O.oracle_ranking(C, 3)
+    assert S == [0, 1, 2]
+    C[1, 0] = -2.9 * u          # now expert 1 cancels expert 0: gold = 0.1 u + v
+    S, errs = O.oracle_ranking(C, 3)
+    # single: e0 = 2.9^2 + 1, e1 = 3^2 + 1, e2 = 0.01 -> 2 ; then {2,0}: 2.9^2, {2,1}: 3^2 -> 0 ; then 1
+    assert S == [2, 0, 1]
+    np.testing.assert_allclose(errs, np.array([0.01, 2.9 ** 2, 0.0]) / 1.01, atol=1e-15)
+
+
+def test_oracle_ranking_ties_and_unused_experts_go_in_id_order():
+    rng = np.random.default_rng(8)
+    C = np.zeros((6, 4, 5))
+    C[4], C[1] = rng.standard_normal((4, 5)), rng.standard_normal((4, 5)) * 0.2
+    S, errs = O.oracle_ranking(C, 6)
+    assert S[:2] == [4, 1] and S[2:] == [0, 2, 3, 5]     # experts that no token uses change nothing: lowest id first
+    assert errs[1] == pytest.approx(0.0, abs=1e-28) and np.all(errs[2:] == errs[1])
+
+
+def test_expert_contributions_sum_to_the_unbudgeted_output_and_feed_the_ranking():
+    rng = np.random.default_rng(6)
+    M, d, N, k, F = 10, 8, 6, 2, 4
+    W = dict(w_router=rng.standard_normal((N, d)), b_router=None, w_gate=rng.standard_normal((N, F, d)) * 0.3,
+             w_up=rng.standard_normal((N, F, d)) * 0.3, w_down=rng.standard_normal((N, d, F)) * 0.3)
+    h = rng.standard_normal((M, d))
+    _, ids, w = O.route(h, W["w_router"], None, k, True)
+    C = O.expert_contributions(h, ids, w, W["w_gate"], W["w_up"], W["w_down"], N)
+    np.testing.assert_allclose(C.sum(axis=0), O.unbudgeted_forward(h, W, k, True), rtol=1e-13, atol=1e-15)
+    for i in range(N):
+        used = {t for t in range(M) if i in ids[t]}
+        assert all((np.any(C[i, t] != 0)) == (t in used) for t in range(M))
+    S, errs = O.oracle_ranking(C, N)
+    # the oracle's error after B picks is never above the truncation error of the router-based shortlist of size B
+    g = O.routing_probs(O.router_logits(h, W["w_router"]))
+    for B in range(1, N + 1):
+        Sr = O.shortlist(O.aggregate_scores(g), B)
+        trunc = O.layer_forward(h, W, k, True, B, O.TRUNCATE)["out"]
+        if B == 1:
+            assert errs[0] <= O.reconstruction_error(trunc, C.sum(axis=0)) + 1e-12
+    assert errs[-1] == pytest.approx(0.0, abs=1e-25)
