@@ -180,6 +180,8 @@ def main():
         # probability held by the top-B experts, and ||O_S - O*||^2 / ||O*||^2 against the B = N output
         full, full_taps = mb.moespec_layer_forward(desc, sets[0], h, cfg.n_experts, policy, ws, taps=True)
         curve = mb.moespec_coverage_curve(desc, full_taps["scores"]).cpu().tolist()
+        # the greedy oracle of Eq. (6) on the same layer: its error after B experts is the floor for any selector
+        oracle_err = mb.moespec_oracle_ranking(desc, sets[0], h, cfg.n_experts, ws)[1].cpu().tolist()
         for b in budgets:
             if policy == mb.SUBSTITUTE and b < cfg.top_k:
                 continue
@@ -189,7 +191,8 @@ def main():
             mb.LayerForwardCall(desc, sets[0], h, b, policy, ws, out)()
             rec = float(mb.moespec_reconstruction_error(desc, out, full, ws)[0].item())
             rows.append({"B": b, "loaded_experts": nl, "coverage": round(curve[b - 1], 4),
-                         "reconstruction_error": round(rec, 5), "ms_per_layer": round(ms, 5),
+                         "reconstruction_error": round(rec, 5),
+                         "oracle_ranking_error": round(oracle_err[b - 1], 5), "ms_per_layer": round(ms, 5),
                          "tokens_per_s": round(M / (ms * 1e-3), 1),
                          "GBps": round(nl * cfg.expert_bytes / (ms * 1e-3) / 1e9, 1),
                          "frac_of_peak": round(nl * cfg.expert_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})

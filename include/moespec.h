@@ -15,7 +15,8 @@
  *
  * and, around that path, the static ranking of Eq. (4) (moespec_calibration_count,
  * moespec_static_shortlist: a shortlist fixed from calibration data, passed in as ext_shortlist)
- * and two analysis quantities of Section 4 (moespec_coverage_curve, moespec_reconstruction_error).
+ * the Oracle ranking of Eq. (6) (moespec_oracle_ranking, an upper bound for analysis) and two analysis
+ * quantities of Section 4 (moespec_coverage_curve, moespec_reconstruction_error).
  *
  * Conventions (all calls)
  *   Pointers  Every buffer pointer is a DEVICE pointer unless it is a descriptor struct
@@ -231,6 +232,22 @@ moespec_status moespec_coverage_curve(const moespec_desc *desc, const double *sc
  */
 moespec_status moespec_reconstruction_error(const moespec_desc *desc, const void *out_budgeted, const void *out_full,
                                             int32_t M, double *err, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Oracle ranking - Eq. (6): runs the layer with natural routing (every expert of the union), then
+ * greedily builds the ordering that minimises the reconstruction error against the gold output
+ * O* = sum_{i in T_k(h_t)} g-bar_i(h_t) E_i(h_t): starting from the empty set, B times add the expert i
+ * outside S that minimises sum_t || O*_t - sum_{j in (S + {i}) and in T_k(h_t)} g-bar_j(h_t) E_j(h_t) ||^2
+ * (ties to the lowest id).  Analysis only: it streams every expert of the union.
+ *   ranking [B] int32  out  experts in the order they were added (an upper-bound shortlist, usable as
+ *                           ext_shortlist)
+ *   err     [B] double out  that error divided by ||O*||^2 after each addition
+ * The selection runs in fp64 on the experts' fp32 outputs.  Requires top_k * 8 <= d_ff * sizeof(dtype)
+ * (MOESPEC_ERR_UNSUPPORTED_SHAPE otherwise).
+ */
+moespec_status moespec_oracle_ranking(const moespec_desc *desc, const moespec_weights *weights, const void *h,
+                                      int32_t M, int32_t B, int32_t *ranking, double *err,
+                                      void *ws, size_t ws_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

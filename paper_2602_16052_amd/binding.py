@@ -25,7 +25,7 @@ TRUNCATE, SUBSTITUTE = 0, 1
 EXPORTS = ("moespec_abi_version", "moespec_status_string", "moespec_check_desc", "moespec_workspace_bytes",
            "moespec_route", "moespec_budget", "moespec_expert_ffn", "moespec_layer_forward",
            "moespec_calibration_count", "moespec_static_shortlist", "moespec_coverage_curve",
-           "moespec_reconstruction_error")
+           "moespec_reconstruction_error", "moespec_oracle_ranking")
 
 
 class MoeSpecError(RuntimeError):
@@ -98,6 +98,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moespec_reconstruction_error.restype = c_int32
     lib.moespec_reconstruction_error.argtypes = [POINTER(Desc), c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
                                                  c_size_t, c_void_p]
+    lib.moespec_oracle_ranking.restype = c_int32
+    lib.moespec_oracle_ranking.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_void_p,
+                                           c_void_p, c_void_p, c_size_t, c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -384,3 +387,16 @@ def moespec_reconstruction_error(desc: LayerDesc, out_budgeted: torch.Tensor, ou
         M, _ptr(err), _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "moespec_reconstruction_error")
     return err
+
+
+def moespec_oracle_ranking(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: torch.Tensor, B: int, ws: torch.Tensor,
+                           stream=None):
+    """Eq. (6): greedy oracle ordering.  Returns (ranking int32 [B], err float64 [B])."""
+    M, dt = h.shape[0], desc.torch_dtype
+    ranking = torch.empty(max(int(B), 1), dtype=torch.int32, device=h.device)
+    err = torch.empty(max(int(B), 1), dtype=torch.float64, device=h.device)
+    cd, cw = desc.c(), _weights(desc, weights, True, True)
+    st = load_library().moespec_oracle_ranking(ctypes.byref(cd), ctypes.byref(cw), _ptr(h, dt, M * desc.d, "h"), M, int(B),
+                                               _ptr(ranking), _ptr(err), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "moespec_oracle_ranking")
+    return ranking, err

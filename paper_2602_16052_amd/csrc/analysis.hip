@@ -101,6 +101,128 @@ __global__ void sqdiff_total_kernel(const double *__restrict__ part, int M, doub
   err[2] = sd;
 }
 
+// ---- Oracle ranking, Eq. (6) ------------------------------------------------------------------------
+// With C_i[t] = w[t, slot] * E_i(h_t) for the slot that routes token t to expert i (zero otherwise) and the
+// gold output O* = sum_i C_i, the error of a set S is ||O*||^2 - 2 sum_{i in S} b_i + sum_{i,j in S} G_ij
+// with G_ij = sum_t <C_i[t], C_j[t]> and b_i = sum_j G_ij.  Adding i to S changes it by
+// G_ii - 2 b_i + 2 sum_{j in S} G_ij, so the greedy choice needs only the Gram matrix.
+
+// pair_gram[t, a, b] = w_a w_b <y[t k + a], y[t k + b]> for the surviving slots a, b of token t (0 otherwise),
+// in fp64; thread i folds the elements i, i + 256, ... in ascending order, then thread 0 the 256 partial sums.
+__global__ __launch_bounds__(256) void pair_gram_kernel(const float *__restrict__ y, int splits, size_t split_stride,
+                                                        const int32_t *__restrict__ tok_ids,
+                                                        const float *__restrict__ tok_w, int k, int d,
+                                                        double *__restrict__ pair_gram) {
+  __shared__ double part[256];
+  const int t = blockIdx.x, tid = threadIdx.x;
+  auto elem = [&](int slot, int j) {
+    const float *p = y + ((size_t)t * k + slot) * d + j;
+    float v = p[0];
+    for (int sp = 1; sp < splits; ++sp) v += p[sp * split_stride];  // same order as the combine
+    return (double)v;
+  };
+  for (int a = 0; a < k; ++a)
+    for (int b = a; b < k; ++b) {
+      const bool live = tok_ids[(size_t)t * k + a] >= 0 && tok_ids[(size_t)t * k + b] >= 0;  // uniform
+      double acc = 0.0;
+      if (live)
+        for (int j = tid; j < d; j += 256) acc += elem(a, j) * elem(b, j);
+      part[tid] = acc;
+      __syncthreads();
+      if (tid == 0) {
+        double s = 0.0;
+        for (int i = 0; i < 256; ++i) s += part[i];
+        s *= (double)tok_w[(size_t)t * k + a] * (double)tok_w[(size_t)t * k + b];
+        pair_gram[((size_t)t * k + a) * k + b] = live ? s : 0.0;
+        pair_gram[((size_t)t * k + b) * k + a] = live ? s : 0.0;
+      }
+      __syncthreads();
+    }
+}
+
+// One workgroup: Gram matrix (tokens added in ascending order), then the greedy selection.
+// gram: [N, N] matrix, then b[N], cross[N], taken[N] (as doubles).
+__global__ __launch_bounds__(kAnalysisThreads) void oracle_greedy_kernel(const double *__restrict__ pair_gram,
+                                                                         const int32_t *__restrict__ tok_ids, int M,
+                                                                         int N, int k, int B, double *gram,
+                                                                         int32_t *__restrict__ ranking,
+                                                                         double *__restrict__ err) {
+  __shared__ double val[kAnalysisThreads];
+  __shared__ int32_t idx[kAnalysisThreads];
+  __shared__ double total_s, err_s;
+  double *G = gram, *bvec = gram + (size_t)N * N, *cross = bvec + N, *taken = cross + N;
+  const int tid = threadIdx.x, nt = blockDim.x;
+  for (size_t i = tid; i < (size_t)N * (N + 3); i += nt) gram[i] = 0.0;
+  __syncthreads();
+  for (int t = 0; t < M; ++t) {  // experts of one token are distinct: no two threads meet on an entry
+    for (int p = tid; p < k * k; p += nt) {
+      const int ea = tok_ids[(size_t)t * k + p / k], eb = tok_ids[(size_t)t * k + p % k];
+      if (ea >= 0 && eb >= 0 && ea < N && eb < N) G[(size_t)ea * N + eb] += pair_gram[(size_t)t * k * k + p];
+    }
+    __syncthreads();
+  }
+  for (int i = tid; i < N; i += nt) {
+    double s = 0.0;
+    for (int j = 0; j < N; ++j) s += G[(size_t)i * N + j];
+    bvec[i] = s;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    double s = 0.0;
+    for (int i = 0; i < N; ++i) s += bvec[i];
+    total_s = s;  // ||O*||^2
+    err_s = s;    // error of the empty set
+  }
+  __syncthreads();
+  for (int step = 0; step < B; ++step) {
+    // candidate of this thread: the best of i = tid, tid + nt, ... (smaller change first, then lower id)
+    double best = INFINITY;
+    int besti = 0x7fffffff;
+    for (int i = tid; i < N; i += nt)
+      if (taken[i] == 0.0) {
+        const double delta = G[(size_t)i * N + i] - 2.0 * bvec[i] + 2.0 * cross[i];
+        if (delta < best || (delta == best && i < besti)) {
+          best = delta;
+          besti = i;
+        }
+      }
+    val[tid] = best;
+    idx[tid] = besti;
+    __syncthreads();
+    for (int s = nt >> 1; s > 0; s >>= 1) {
+      if (tid < s) {
+        const double o = val[tid + s];
+        const int oi = idx[tid + s];
+        if (o < val[tid] || (o == val[tid] && oi < idx[tid])) {
+          val[tid] = o;
+          idx[tid] = oi;
+        }
+      }
+      __syncthreads();
+    }
+    const int pick = idx[0];
+    if (tid == 0) {
+      err_s += val[0];
+      ranking[step] = pick;
+      err[step] = err_s / total_s;
+      taken[pick] = 1.0;
+    }
+    for (int i = tid; i < N; i += nt) cross[i] += G[(size_t)i * N + pick];
+    __syncthreads();
+  }
+}
+
+hipError_t launch_oracle_ranking(const moespec_desc &ds, const float *y, int splits, size_t split_stride,
+                                 const int32_t *tok_ids, const float *tok_w, int M, int B, double *pair_gram,
+                                 double *gram, int32_t *ranking, double *err, hipStream_t st) {
+  pair_gram_kernel<<<M, 256, 0, st>>>(y, splits, split_stride, tok_ids, tok_w, ds.top_k, ds.d, pair_gram);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  oracle_greedy_kernel<<<1, kAnalysisThreads, 0, st>>>(pair_gram, tok_ids, M, ds.n_experts, ds.top_k, B, gram, ranking,
+                                                       err);
+  return hipGetLastError();
+}
+
 hipError_t launch_calibration_count(const int32_t *topk_ids, int M, int k, int N, int64_t *counts, hipStream_t st) {
   const int n = M * k;
   int blocks = (n + 255) / 256;

@@ -199,4 +199,32 @@ moespec_status moespec_reconstruction_error(const moespec_desc *desc, const void
                                               static_cast<hipStream_t>(hip_stream)));
 }
 
+moespec_status moespec_oracle_ranking(const moespec_desc *desc, const moespec_weights *weights, const void *h,
+                                      int32_t M, int32_t B, int32_t *ranking, double *err, void *ws, size_t ws_bytes,
+                                      void *hip_stream) {
+  moespec_status s = check_common(desc, M, ws, ws_bytes);
+  if (s != MOESPEC_OK) return s;
+  if ((s = check_weights(weights, true, true)) != MOESPEC_OK) return s;
+  if (B < 1 || B > desc->n_experts || !h || !aligned16(h) || !ranking || !err) return MOESPEC_ERR_INVALID_ARG;
+  // the per-token k x k Gram blocks (doubles) borrow the act buffer once the down pass has read it
+  const size_t es = desc->dtype == MOESPEC_BF16 ? 2 : 4;
+  if ((size_t)desc->top_k * 8 > (size_t)desc->d_ff * es) return MOESPEC_ERR_UNSUPPORTED_SHAPE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  Workspace w = carve_workspace(*desc, M, ws);
+  const int N = desc->n_experts;
+  // natural routing (Eq. (2)): the budgeted path with B = N and truncation keeps every token's top-k
+  const bool self_seg = expert_ffn_self_segmenting(*desc, M);
+  hipError_t e = launch_route(*desc, *weights, h, M, w.probs, nullptr, nullptr, w.done, 1 + N, st);
+  if (e != hipSuccess) return MOESPEC_ERR_HIP;
+  e = launch_budget(*desc, w.probs, M, N, MOESPEC_TRUNCATE, nullptr, nullptr, w.budget_ids, w.tok_ids, w.tok_w,
+                    w.seg_expert, w.seg_off, w.perm, nullptr, w.items, w.done, true, !self_seg, st);
+  if (e != hipSuccess) return MOESPEC_ERR_HIP;
+  e = launch_expert_ffn(*desc, *weights, h, M, N, w.seg_expert, w.seg_off, w.perm, w.tok_ids, w.tok_w, nullptr,
+                        nullptr, w.act, w.y, w.items, !self_seg, self_seg ? w.done + 1 : nullptr, w.budget_ids, st);
+  if (e != hipSuccess) return MOESPEC_ERR_HIP;
+  return from_hip(launch_oracle_ranking(*desc, w.y, down_splits(*desc, N), (size_t)M * desc->top_k * desc->d,
+                                        w.tok_ids, w.tok_w, M, B, static_cast<double *>(w.act), w.gram, ranking, err,
+                                        st));
+}
+
 }  // extern "C"

@@ -126,6 +126,7 @@ struct Workspace {
   int32_t *done;      // [1 + N] ticket counter of the budget stage, then surviving pairs per shortlist rank
   void *act;          // [M * k, F] dtype
   float *y;           // [kMaxDownSplits][M * k, d]
+  double *gram;       // [N, N + 3] scratch of the oracle ranking
   size_t bytes;
 };
 
@@ -153,6 +154,7 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
   w.done = static_cast<int32_t *>(take(sizeof(int32_t) * (1 + N)));
   w.act = take(es * M * k * F);
   w.y = static_cast<float *>(take(sizeof(float) * kMaxDownSplits * M * k * d));
+  w.gram = static_cast<double *>(take(sizeof(double) * N * (N + 3)));
   w.bytes = off;
   return w;
 }
@@ -182,10 +184,18 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                              float *y, int4 *items, bool items_ready, const int32_t *rank_count,
                              const int32_t *shortlist, hipStream_t st, void *const *trace = nullptr);
 bool expert_ffn_self_segmenting(const moespec_desc &ds, int M);
+// Number of K-split copies of y that launch_expert_ffn writes for n_seg segments; out == NULL there skips
+// the combine and leaves the per-pair expert outputs in y.
+int down_splits(const moespec_desc &ds, int n_seg);
 // Analysis kernels (analysis.hip).  part: 2 M doubles of scratch.
 hipError_t launch_calibration_count(const int32_t *topk_ids, int M, int k, int N, int64_t *counts, hipStream_t st);
 hipError_t launch_static_shortlist(const int64_t *counts, int N, int B, int32_t *shortlist, hipStream_t st);
 hipError_t launch_coverage_curve(const double *scores, int N, double *curve, hipStream_t st);
+// Greedy oracle ranking on the per-pair outputs y (splits copies, split_stride floats apart) of a run with
+// natural routing (tok_ids / tok_w = natural top-k).  pair_gram: M k k doubles, gram: N N + 3 N doubles of scratch.
+hipError_t launch_oracle_ranking(const moespec_desc &ds, const float *y, int splits, size_t split_stride,
+                                 const int32_t *tok_ids, const float *tok_w, int M, int B, double *pair_gram,
+                                 double *gram, int32_t *ranking, double *err, hipStream_t st);
 hipError_t launch_reconstruction_error(const moespec_desc &ds, const void *out_budgeted, const void *out_full, int M,
                                        double *part, double *err, hipStream_t st);
 

@@ -706,6 +706,20 @@ bool expert_ffn_self_segmenting(const moespec_desc &ds, int M) {
          M <= kSelfMaxTokens && ds.top_k <= kSelfMaxK;
 }
 
+// K-split of the LDS-tiled down pass: when its (segment, row tile) items alone cannot give every compute
+// unit two workgroups, each item is cut along F into up to kMaxDownSplits parts with their own copy of y,
+// as long as a part keeps at least 16 chunks (shorter walks are dominated by their start-up: measured
+// slower at F = 1024, 1.6x to 2.7x faster at F = 14336 with 4 or 2 loaded experts).
+int down_splits(const moespec_desc &ds, int n_seg) {
+  int splits = 1;
+  if (ds.dtype == MOESPEC_BF16 && ds.d_ff % 128 == 0) {
+    const int tiles = (ds.d / 32 + kFfnWaves - 1) / kFfnWaves;
+    while (splits < kMaxDownSplits && (long long)n_seg * tiles * splits * 2 <= 512 && ds.d_ff / 128 >= 32 * splits)
+      splits *= 2;
+  }
+  return splits;
+}
+
 static int pick_unroll(int K) { return K % 128 == 0 ? 4 : (K % 64 == 0 ? 2 : 1); }
 
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
@@ -724,15 +738,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
   auto mark = [&](int i) {
     if (trace && trace[i]) (void)hipEventRecord(static_cast<hipEvent_t>(trace[i]), st);
   };
-  // K-split of the LDS-tiled down pass: when its (segment, row tile) items alone cannot give every compute
-  // unit two workgroups, each item is cut along F into up to kMaxDownSplits parts with their own copy of y,
-  // as long as a part keeps at least 16 chunks (shorter walks are dominated by their start-up: measured
-  // slower at F = 1024, 1.6x to 2.7x faster at F = 14336 with 4 or 2 loaded experts).
-  int splits = 1;
-  if (ds.dtype == MOESPEC_BF16 && F % 128 == 0) {
-    const int tiles = (d / 32 + kFfnWaves - 1) / kFfnWaves;
-    while (splits < kMaxDownSplits && (long long)n_seg * tiles * splits * 2 <= 512 && F / 128 >= 32 * splits) splits *= 2;
-  }
+  const int splits = down_splits(ds, n_seg);
   const size_t split_stride = (size_t)M * k * d;
   if (ds.dtype == MOESPEC_BF16) {
     for (int pass = 1; pass <= 2; ++pass) {
@@ -762,6 +768,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
       if (e != hipSuccess) return e;
       mark(pass - 1);
     }
+    if (!out) return hipSuccess;  // the caller only wants the per-pair outputs y
     dim3 cgrid((d / 4 + 255) / 256, M);
     combine_kernel<uint16_t><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const uint16_t *>(residual), k, d,
                                                     splits, split_stride, static_cast<uint16_t *>(out));
@@ -782,6 +789,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                                                   ds.n_experts, k, d, F, y);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   mark(1);
+  if (!out) return hipSuccess;
   dim3 cgrid((d / 4 + 255) / 256, M);
   combine_kernel<float><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const float *>(residual), k, d, 1,
                                                split_stride, static_cast<float *>(out));

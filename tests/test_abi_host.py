@@ -141,6 +141,20 @@ def test_analysis_calls_reject_bad_arguments(lib):
     assert lib.moespec_reconstruction_error(ctypes.byref(cd), P, P, 8, None, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
 
 
+def test_oracle_ranking_rejects_bad_arguments(lib):
+    d = D()
+    cd = d.c()
+    w = mb.Weights(0x40000, None, 0x40000, 0x40000, 0x40000)
+    wsb = mb.workspace_bytes(d, 8)
+    P = 0x50000
+    f = lib.moespec_oracle_ranking
+    assert f(ctypes.byref(cd), ctypes.byref(w), P, 8, 0, P, P, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    assert f(ctypes.byref(cd), ctypes.byref(w), P, 8, d.n_experts + 1, P, P, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    assert f(ctypes.byref(cd), ctypes.byref(w), P, 8, 4, None, P, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    assert f(ctypes.byref(cd), ctypes.byref(w), P, 8, 4, P, P, 0x10000, 64, None) == mb.ERR_WORKSPACE_TOO_SMALL
+    assert f(ctypes.byref(cd), None, P, 8, 4, P, P, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     d = D()

@@ -107,3 +107,42 @@ def test_coverage_curve_and_reconstruction_error(case):
             assert abs(e[0] - want_o) <= 0.05 * max(want_o, 1e-3)
             errs.append(e[0])
     assert max(errs) > 0
+
+
+def test_oracle_ranking_matches_the_cpu_greedy(case):
+    """Eq. (6).  fp32 layers: same ordering and error curve.  bf16 layers (expert outputs carry ~1e-3 of bf16
+    rounding): every pick must be a minimiser of the oracle's own error up to that rounding, and the error
+    curve must agree."""
+    c = case
+    cfg, desc = c["cfg"], c["desc"]
+    N = cfg.n_experts
+    ranking, err = mb.moespec_oracle_ranking(desc, c["W_d"], c["h_d"], N, c["ws"])
+    torch.cuda.synchronize()
+    ranking, err = ranking.cpu().tolist(), err.cpu().numpy()
+    _, ids, w = O.route(c["h_o"], c["W_o"]["w_router"], c["W_o"]["b_router"], cfg.top_k, cfg.renorm)
+    C = O.expert_contributions(c["h_o"], ids, w, c["W_o"]["w_gate"], c["W_o"]["w_up"], c["W_o"]["w_down"], N)
+    S, errs = O.oracle_ranking(C, N)
+    assert sorted(ranking) == list(range(N))
+    union = O.expert_union(ids)
+    tol = 1e-5 if cfg.dtype == "f32" else 2e-2
+    np.testing.assert_allclose(err, errs, atol=tol * 0.1, rtol=tol)
+    assert err[len(union) - 1] <= tol * 0.1 and set(ranking[:len(union)]) == set(union)
+    assert ranking[len(union):] == sorted(set(range(N)) - set(union))      # unused experts last, in id order
+    if cfg.dtype == "f32":
+        assert ranking == S
+    # each GPU pick, judged by the oracle's arithmetic on the oracle's contributions
+    gold = C.sum(axis=0)
+    denom = float(np.sum(gold * gold))
+    partial = np.zeros_like(gold)
+    for step in range(len(union)):
+        cand = {i: float(np.sum((gold - partial - C[i]) ** 2)) / denom for i in range(N) if i not in ranking[:step]}
+        assert cand[ranking[step]] <= min(cand.values()) + tol * 0.1
+        partial = partial + C[ranking[step]]
+    # the ordering is usable as an external shortlist
+    B = cfg.budgets[0]
+    out = mb.moespec_layer_forward(desc, c["W_d"], c["h_d"], B, mb.TRUNCATE, c["ws"],
+                                   ext_shortlist=torch.tensor(ranking[:B], dtype=torch.int32, device="cuda"))
+    full = mb.moespec_layer_forward(desc, c["W_d"], c["h_d"], N, mb.TRUNCATE, c["ws"])
+    e = mb.moespec_reconstruction_error(desc, out, full, c["ws"])
+    torch.cuda.synchronize()
+    assert float(e[0]) == pytest.approx(float(err[B - 1]), abs=3 * tol, rel=0.2)
