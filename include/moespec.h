@@ -29,6 +29,8 @@
  *             (a hipStream_t passed as void*; NULL = the default stream) and returns without
  *             synchronising.  Nothing is copied to the host; data-dependent quantities (the number
  *             of loaded experts, segment sizes) stay on the device.
+ *   Sizes     1 <= M <= 65535 tree tokens per call, and M * top_k * max(d, d_ff) < 2^31
+ *             (MOESPEC_ERR_UNSUPPORTED_SHAPE beyond that).
  *   Workspace `ws` must hold at least moespec_workspace_bytes(desc, M) bytes, 256-byte aligned.
  *             Its contents are scratch: undefined before and after a call.  Calls that share a
  *             workspace must be ordered on one stream.
@@ -90,7 +92,7 @@ const char *moespec_status_string(int32_t status);
 
 /*
  * Checks that the kernels cover this layer shape: d and d_ff multiples of 32 (bf16) or 4 (f32),
- * d <= 8192, 1 <= top_k <= n_experts <= 1024, top_k <= 64, n_experts * d_ff * d < 2^40, dtype and
+ * d <= 8192, d_ff <= 2^20, 1 <= top_k <= n_experts <= 1024, top_k <= 64, n_experts * d_ff * d < 2^40, dtype and
  * renorm valid.
  * Returns MOESPEC_OK, MOESPEC_ERR_INVALID_ARG or MOESPEC_ERR_UNSUPPORTED_SHAPE.  Host only.
  */

@@ -9,6 +9,7 @@ namespace {
 constexpr int kMaxExperts = 1024;
 constexpr int kMaxTopK = 64;
 constexpr int kMaxHidden = 8192;
+constexpr int kMaxInter = 1 << 20;
 constexpr int kMaxTokens = 65535;
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -19,7 +20,7 @@ moespec_status check_desc(const moespec_desc *ds) {
   if (ds->renorm != 0 && ds->renorm != 1) return MOESPEC_ERR_INVALID_ARG;
   if (ds->d < 1 || ds->d_ff < 1 || ds->n_experts < 1) return MOESPEC_ERR_INVALID_ARG;
   if (ds->top_k < 1 || ds->top_k > ds->n_experts) return MOESPEC_ERR_INVALID_ARG;
-  if (ds->n_experts > kMaxExperts || ds->top_k > kMaxTopK || ds->d > kMaxHidden)
+  if (ds->n_experts > kMaxExperts || ds->top_k > kMaxTopK || ds->d > kMaxHidden || ds->d_ff > kMaxInter)
     return MOESPEC_ERR_UNSUPPORTED_SHAPE;
   const int mult = ds->dtype == MOESPEC_BF16 ? 32 : 4;
   if (ds->d % mult != 0 || ds->d_ff % mult != 0) return MOESPEC_ERR_UNSUPPORTED_SHAPE;
@@ -31,6 +32,9 @@ moespec_status check_common(const moespec_desc *ds, int32_t M, const void *ws, s
   moespec_status s = check_desc(ds);
   if (s != MOESPEC_OK) return s;
   if (M < 1 || M > kMaxTokens) return MOESPEC_ERR_INVALID_ARG;
+  // the kernels index the per-pair intermediates with 32-bit element offsets
+  if ((int64_t)M * ds->top_k * (ds->d > ds->d_ff ? ds->d : ds->d_ff) >= ((int64_t)1 << 31))
+    return MOESPEC_ERR_UNSUPPORTED_SHAPE;
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOESPEC_ERR_INVALID_ARG;
   if (ws_bytes < carve_workspace(*ds, M, nullptr).bytes) return MOESPEC_ERR_WORKSPACE_TOO_SMALL;
   return MOESPEC_OK;

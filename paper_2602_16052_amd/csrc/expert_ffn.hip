@@ -42,6 +42,10 @@ __device__ __forceinline__ int pair_index(const int32_t *perm, int pos, int M, i
   return q < 0 ? 0 : (q >= M * k ? M * k - 1 : q);
 }
 
+// base + a 32-bit byte offset: with a uniform base the load needs one offset register, not a 64-bit address
+__device__ __forceinline__ const uint16_t *at_bytes(const uint16_t *base, uint32_t bytes) {
+  return reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(base) + bytes);
+}
 __device__ __forceinline__ bf16x8 ld_frag(const uint16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
 // Weight bytes are read exactly once: load them with the non-temporal hint so that the stream does
 // not push the (re-read) token rows out of the caches.
@@ -285,35 +289,42 @@ struct Chunk {
   static __device__ __forceinline__ int swz(int row, int piece) { return row * RB + ((piece ^ (row & (CPR - 1))) << 4); }
 };
 
+// The wave index is taken through readfirstlane in these kernels: it is uniform within a wave, and the
+// compiler then keeps everything derived from it (row offsets, tile bases) in scalar registers.
 constexpr int kLdsBytes = 65536;  // 32 KB of wave-private weight tiles + 2 x 16 KB token tile (or 16 + 2 x 16)
 
 // One workgroup pass over K for NT token tiles.  wt0 / wt1: first row of this wave's two 16-row weight
-// tiles (row stride K elements).  xsrc[q]: this lane's source row (already offset by its 16-byte piece)
+// tiles (row stride K elements).  xbase + xsrc[q] bytes: this lane's source row (already at its 16-byte piece)
 // for its q-th share of the token tile.  Accumulates acc0[j] (tile 0) and acc1[j] (tile 1) over the K range
 // [kb, kb + kl) of the rows (row stride K).
 template <int NT, int U>
 __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt1, int K, int kb, int kl, int ks,
-                                         const uint16_t *const (&xsrc)[NT * U / 4], unsigned char *lds,
+                                         const uint16_t *xbase, const uint32_t (&xsrc)[NT * U / 4], unsigned char *lds,
                                          f32x4 (&acc0)[NT], f32x4 (&acc1)[NT]) {
   using C = Chunk<U>;
   constexpr int IPW = NT * U / 4;  // token-tile loads per wave per chunk (4 waves share the tile)
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   unsigned char *a_lds = lds + wave * 2 * C::TILE;                 // wave-private: two weight tiles
   unsigned char *x_lds = lds + kFfnWaves * 2 * C::TILE;            // shared: 2 buffers of NT*16 rows
   constexpr int XBUF = NT * 16 * C::RB;
+  // two token-tile buffers if they fit beside the weight tiles, else one (and a second barrier per chunk)
+  constexpr bool kDoubleX = kFfnWaves * 2 * C::TILE + 2 * XBUF <= kLdsBytes;
 
   // global -> register staging
+  // uniform base + 32-bit byte offset per lane (a tile is 16 rows of at most 2^20 elements): the loads need
+  // one offset register each instead of a 64-bit address
   const int lrow = lane / C::CPR, lpc = lane % C::CPR;
+  const uint32_t lane_off = 2u * ((uint32_t)lrow * (uint32_t)K + (uint32_t)lpc * 8u);
   bf16x8 GA[2][U], GX[IPW];
   auto issue = [&](int k) {
 #pragma unroll
     for (int q = 0; q < U; ++q) {
-      const size_t off = (size_t)(q * C::RPI + lrow) * K + k + lpc * 8;
-      GA[0][q] = ld_stream(wt0 + off);
-      GA[1][q] = ld_stream(wt1 + off);
+      const uint32_t off = lane_off + 2u * ((uint32_t)(q * C::RPI) * (uint32_t)K + (uint32_t)k);
+      GA[0][q] = ld_stream(at_bytes(wt0, off));
+      GA[1][q] = ld_stream(at_bytes(wt1, off));
     }
 #pragma unroll
-    for (int q = 0; q < IPW; ++q) GX[q] = ld_frag(xsrc[q] + k);
+    for (int q = 0; q < IPW; ++q) GX[q] = ld_frag(at_bytes(xbase, xsrc[q] + 2u * (uint32_t)k));
   };
   auto park = [&](int buf) {
 #pragma unroll
@@ -350,12 +361,13 @@ __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt
   int k = ((ks % kl) / C::KC) * C::KC;
   issue(kb + k);
   for (int i = 0; i < nst; ++i) {
-    park(i & 1);
+    park(kDoubleX ? (i & 1) : 0);
     k += C::KC;
     k = k >= kl ? k - kl : k;
     if (i + 1 < nst) issue(kb + k);
     __syncthreads();  // token tile i complete; also orders this wave's tile writes before its reads
-    compute(i & 1);
+    compute(kDoubleX ? (i & 1) : 0);
+    if (!kDoubleX) __syncthreads();  // everybody has read the single token tile before it is overwritten
   }
   __syncthreads();  // the LDS tiles may be reused by the caller's next pass
 }
@@ -432,19 +444,19 @@ __device__ __forceinline__ void gateup_lds(const uint16_t *wt0, const uint16_t *
                                            int f0, int ks, unsigned char *lds, uint16_t *__restrict__ act) {
   using C = Chunk<U>;
   constexpr int IPW = NT * U / 4;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint16_t *xsrc[IPW];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint32_t xsrc[IPW];  // 32-bit byte offsets: M * d < 2^31 elements (checked on the host)
 #pragma unroll
   for (int q = 0; q < IPW; ++q) {
     const int g = (wave * IPW + q) * 64 + lane;
     int p = c0 + g / C::CPR;
     p = p < m ? p : m - 1;  // pad rows repeat the last token; their columns are never stored
-    xsrc[q] = h + (size_t)(pair_at(plist, p, n_pairs) / k) * d + (g % C::CPR) * 8;
+    xsrc[q] = 2u * ((uint32_t)(pair_at(plist, p, n_pairs) / k) * (uint32_t)d + (uint32_t)(g % C::CPR) * 8u);
   }
   f32x4 accg[NT], accu[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) accg[j] = accu[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  lds_pass<NT, U>(wt0, wt1, d, 0, d, ks, xsrc, lds, accg, accu);
+  lds_pass<NT, U>(wt0, wt1, d, 0, d, ks, h, xsrc, lds, accg, accu);
   const int col = lane & 15, kg = lane >> 4;
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
@@ -484,7 +496,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
     if (it.x < 0 || !segment_ok(e, it.z, m, M, N, k)) return;
     plist = perm + it.z;
   }
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // F is a multiple of 32 but a workgroup covers 64 gate rows: the waves of a last, partial workgroup
   // redo rows of the previous tile (same values, same destination) so that every wave reaches the barriers.
   int f0 = (tile * kFfnWaves + wave) * 16;
@@ -498,7 +510,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
     if (mc <= 16) gateup_lds<1, 4>(wt0, wt1, h, plist, n_pairs, k, d, F, c0, m, f0, ks, lds, act);
     else if (mc <= 32) gateup_lds<2, 4>(wt0, wt1, h, plist, n_pairs, k, d, F, c0, m, f0, ks, lds, act);
     else if (mc <= 64) gateup_lds<4, 4>(wt0, wt1, h, plist, n_pairs, k, d, F, c0, m, f0, ks, lds, act);
-    else gateup_lds<8, 2>(wt0, wt1, h, plist, n_pairs, k, d, F, c0, m, f0, ks, lds, act);
+    else gateup_lds<8, 4>(wt0, wt1, h, plist, n_pairs, k, d, F, c0, m, f0, ks, lds, act);
   }
 }
 
@@ -508,19 +520,19 @@ __device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt
                                          int j0, int ks, unsigned char *lds, float *__restrict__ y) {
   using C = Chunk<U>;
   constexpr int IPW = NT * U / 4;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint16_t *xsrc[IPW];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint32_t xsrc[IPW];  // 32-bit byte offsets: M * k * F < 2^31 elements (checked on the host)
 #pragma unroll
   for (int q = 0; q < IPW; ++q) {
     const int g = (wave * IPW + q) * 64 + lane;
     int p = c0 + g / C::CPR;
     p = p < m ? p : m - 1;
-    xsrc[q] = act + (size_t)pair_at(plist, p, n_pairs) * F + (g % C::CPR) * 8;
+    xsrc[q] = 2u * ((uint32_t)pair_at(plist, p, n_pairs) * (uint32_t)F + (uint32_t)(g % C::CPR) * 8u);
   }
   f32x4 acc0[NT], acc1[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) acc0[j] = acc1[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  lds_pass<NT, U>(wt0, wt1, F, kb, kl, ks, xsrc, lds, acc0, acc1);
+  lds_pass<NT, U>(wt0, wt1, F, kb, kl, ks, act, xsrc, lds, acc0, acc1);
   const int col = lane & 15, kg = lane >> 4;
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
@@ -557,7 +569,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
     if (it.x < 0 || !segment_ok(e, it.z, m, M, N, k)) return;
     plist = perm + it.z;
   }
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int sp = tile % splits;
   tile /= splits;
   int j0 = (tile * kFfnWaves + wave) * 32;
@@ -574,7 +586,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
     if (mc <= 16) down_lds<1, 4>(wt0, wt1, act, plist, n_pairs, d, F, kb, kl, c0, m, j0, ks, lds, y);
     else if (mc <= 32) down_lds<2, 4>(wt0, wt1, act, plist, n_pairs, d, F, kb, kl, c0, m, j0, ks, lds, y);
     else if (mc <= 64) down_lds<4, 4>(wt0, wt1, act, plist, n_pairs, d, F, kb, kl, c0, m, j0, ks, lds, y);
-    else down_lds<8, 2>(wt0, wt1, act, plist, n_pairs, d, F, kb, kl, c0, m, j0, ks, lds, y);
+    else down_lds<8, 4>(wt0, wt1, act, plist, n_pairs, d, F, kb, kl, c0, m, j0, ks, lds, y);
   }
 }
 
