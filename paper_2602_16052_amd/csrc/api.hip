@@ -105,7 +105,7 @@ moespec_status moespec_budget(const moespec_desc *desc, const double *probs, int
   return from_hip(launch_budget(*desc, probs, M, B, policy, ext_shortlist, scores,
                                 budget_ids ? budget_ids : w.budget_ids, tok_ids, tok_w,
                                 seg_expert, seg_off, perm, n_loaded, w.items, w.done, false, true,
-                                static_cast<hipStream_t>(hip_stream)));
+                                w.scores, static_cast<hipStream_t>(hip_stream)));
 }
 
 moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weights *weights, const void *h, int32_t M,
@@ -158,7 +158,7 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(1);
   e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, budget_ids, tok_ids, tok_w, seg_expert,
-                    seg_off, perm, t.n_loaded, w.items, w.done, true, want_segments, st);
+                    seg_off, perm, t.n_loaded, w.items, w.done, true, want_segments, w.scores, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(2);
   e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
@@ -221,7 +221,7 @@ moespec_status moespec_oracle_ranking(const moespec_desc *desc, const moespec_we
   hipError_t e = launch_route(*desc, *weights, h, M, w.probs, nullptr, nullptr, w.done, 1 + N, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   e = launch_budget(*desc, w.probs, M, N, MOESPEC_TRUNCATE, nullptr, nullptr, w.budget_ids, w.tok_ids, w.tok_w,
-                    w.seg_expert, w.seg_off, w.perm, nullptr, w.items, w.done, true, !self_seg, st);
+                    w.seg_expert, w.seg_off, w.perm, nullptr, w.items, w.done, true, !self_seg, w.scores, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   e = launch_expert_ffn(*desc, *weights, h, M, N, w.seg_expert, w.seg_off, w.perm, w.tok_ids, w.tok_w, nullptr,
                         nullptr, w.act, w.y, w.items, !self_seg, self_seg ? w.done + 1 : nullptr, w.budget_ids, st);

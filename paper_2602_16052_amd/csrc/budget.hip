@@ -7,6 +7,7 @@
 namespace moespec {
 
 constexpr int kBudgetThreads = 1024;
+constexpr int kRedundantScoreTokens = 1024;
 
 // s_i = sum over t = 0..M-1 of probs[t, i], added strictly in ascending t; the loads of up to 32 rows
 // are issued together so that the chain is bound by the adds, not by memory latency.
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
     const int32_t *__restrict__ ext_shortlist, double *__restrict__ scores, int32_t *__restrict__ budget_ids,
     int32_t *__restrict__ seg_expert, int32_t *tok_ids, float *__restrict__ tok_w, int32_t *__restrict__ seg_off,
     int32_t *__restrict__ perm, int32_t *__restrict__ n_loaded, int4 *__restrict__ items, int staged,
-    int want_segments, int32_t *done) {
+    int want_segments, const double *__restrict__ scores_in, int32_t *done) {
   extern __shared__ __align__(16) unsigned char smem[];
   double *s = reinterpret_cast<double *>(smem);                  // [N] aggregate scores
   double *g = s + N;                                              // [N] this token's probabilities
@@ -138,13 +139,14 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
   }
   if (ext_shortlist == nullptr) {
     // Eq. (5): s_i = sum over the M tree tokens of g_i(h_t), tokens in ascending order.
-    for (int i = tid; i < N; i += blockDim.x) s[i] = column_sum(probs, M, N, i);
+    // (large trees: summed once by scores_kernel instead of by every workgroup)
+    for (int i = tid; i < N; i += blockDim.x) s[i] = scores_in ? scores_in[i] : column_sum(probs, M, N, i);
     __syncthreads();
     select_topk(s, nullptr, N, B, S, rank);
   } else {
     for (int r = tid; r < B; r += blockDim.x) S[r] = ext_shortlist[r];
     if (scores && t == 0)
-      for (int i = tid; i < N; i += blockDim.x) s[i] = column_sum(probs, M, N, i);
+      for (int i = tid; i < N; i += blockDim.x) s[i] = scores_in ? scores_in[i] : column_sum(probs, M, N, i);
   }
   __syncthreads();
   for (int r = tid; r < B; r += blockDim.x)
@@ -220,6 +222,14 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
                  reinterpret_cast<int32_t *>(smem));
 }
 
+// Eq. (5) once for the whole tree (same order of additions as column_sum): used when the tree is so large
+// that recomputing the scores in every workgroup of budget_kernel would dominate.
+__global__ __launch_bounds__(64) void scores_kernel(const double *__restrict__ probs, int M, int N,
+                                                    double *__restrict__ scores) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < N) scores[i] = column_sum(probs, M, N, i);
+}
+
 __global__ void zero_words_kernel(int32_t *p, int n) {
   for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
 }
@@ -227,19 +237,28 @@ __global__ void zero_words_kernel(int32_t *p, int n) {
 hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
                          const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
-                         int4 *items, int32_t *done, bool done_is_zero, bool want_segments, hipStream_t st) {
+                         int4 *items, int32_t *done, bool done_is_zero, bool want_segments, double *score_scratch,
+                         hipStream_t st) {
   const int N = ds.n_experts, k = ds.top_k;
   if (!done_is_zero) {
     zero_words_kernel<<<1, 256, 0, st>>>(done, 1 + N);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
+  // above this many tokens the redundant per-workgroup scoring (M^2 N loads in total) is replaced by one pass
+  const double *scores_in = nullptr;
+  if (M > kRedundantScoreTokens && (ext_shortlist == nullptr || scores != nullptr)) {
+    scores_kernel<<<(N + 63) / 64, 64, 0, st>>>(probs, M, N, score_scratch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    scores_in = score_scratch;
+  }
   const int staged = (size_t)M * k <= 8192;
   const size_t smem_sel = sizeof(double) * (2 * N + ((k + 1) & ~1) + 2) + sizeof(int32_t) * (k + B + 2 * N + 1) + N;
   const size_t smem_seg = sizeof(int32_t) * (3 * B + 1 + (staged ? (size_t)M * k : 0));
   budget_kernel<<<M, kBudgetThreads, smem_sel > smem_seg ? smem_sel : smem_seg, st>>>(
       probs, M, N, k, B, policy, ds.renorm, ext_shortlist, scores, budget_ids, seg_expert, tok_ids, tok_w, seg_off, perm,
-      n_loaded, items, staged, want_segments ? 1 : 0, done);
+      n_loaded, items, staged, want_segments ? 1 : 0, scores_in, done);
   return hipGetLastError();
 }
 

@@ -166,11 +166,12 @@ hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const
 // done: [1 + N] counters (ticket, then the number of surviving pairs of the expert at each shortlist
 // rank), zero at launch or zeroed first (done_is_zero == false).  budget_ids must not be NULL.
 // want_segments == false skips seg_off / perm / n_loaded / items: the expert passes can then only run in
-// the mode that derives its segments from done + 1, budget_ids and tok_ids.
+// the mode that derives its segments from done + 1, budget_ids and tok_ids.  score_scratch: N doubles.
 hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int B, int policy,
                          const int32_t *ext_shortlist, double *scores, int32_t *budget_ids, int32_t *tok_ids,
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
-                         int4 *items, int32_t *done, bool done_is_zero, bool want_segments, hipStream_t st);
+                         int4 *items, int32_t *done, bool done_is_zero, bool want_segments, double *score_scratch,
+                         hipStream_t st);
 // items: table of the non-empty segments ([n_seg + 1] int4 of scratch); items_ready says that the budget
 // stage has already filled it from the same segment arrays, otherwise it is built first.
 // rank_count, shortlist (may be NULL): the shortlist in rank order ([n_seg]) and the surviving pairs of each

@@ -37,6 +37,9 @@ SMALL = {
     # (M k > 8192), several 128-pair rounds per segment
     "s_bf16_m5000": wl.small_config("s_bf16_m5000", "bf16", d=128, n_experts=6, top_k=2, d_ff=128, M=5000,
                                     budgets=(2, 4, 6), bias_alpha=0.4),
+    # a very large tree: the aggregate scores are summed once instead of in every workgroup
+    "s_bf16_m20000": wl.small_config("s_bf16_m20000", "bf16", d=64, n_experts=8, top_k=2, d_ff=64, M=20000,
+                                     budgets=(3, 8), bias_alpha=0.4),
     # the largest expert count and top-k the descriptor check admits
     "s_bf16_n1024": wl.small_config("s_bf16_n1024", "bf16", d=64, n_experts=1024, top_k=64, d_ff=32, M=9,
                                     budgets=(64, 300, 1024), bias_alpha=0.7),
