@@ -7,7 +7,7 @@
 namespace moespec {
 
 constexpr int kBudgetThreads = 1024;
-constexpr int kRedundantScoreTokens = 1024;
+constexpr int kRedundantScoreTokens = 256;
 
 // s_i = sum over t = 0..M-1 of probs[t, i], added strictly in ascending t; the loads of up to 32 rows
 // are issued together so that the chain is bound by the adds, not by memory latency.
@@ -19,6 +19,41 @@ __device__ __forceinline__ double column_sum(const double *__restrict__ probs, i
     for (int u = 0; u < 32; ++u) v[u] = t + u < M ? probs[(size_t)(t + u) * N + i] : 0.0;
 #pragma unroll
     for (int u = 0; u < 32; ++u) acc += v[u];  // rows past M add +0.0, which leaves the sum unchanged
+  }
+  return acc;
+}
+
+// The same sums for all N columns by a whole workgroup (N <= blockDim.x): the rows are fetched `rows_per_chunk`
+// at a time with every thread loading (contiguous, one latency per chunk, the next chunk already in flight),
+// parked in LDS, and thread i then adds column i row by row - the additions keep the strict ascending order,
+// only the memory latency leaves the chain.  tab: rows_per_chunk * N doubles of LDS.  Synchronises.
+constexpr int kScoreLoads = 4;  // values per thread and chunk
+__device__ __forceinline__ double column_sums_staged(const double *__restrict__ probs, int M, int N,
+                                                     int rows_per_chunk, double *tab) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  double nxt[kScoreLoads];
+  auto fetch = [&](int t0) {
+    const int n = (M - t0 < rows_per_chunk ? M - t0 : rows_per_chunk) * N;
+#pragma unroll
+    for (int u = 0; u < kScoreLoads; ++u) {
+      const int idx = tid + u * nt;
+      nxt[u] = idx < n ? probs[(size_t)t0 * N + idx] : 0.0;
+    }
+  };
+  double acc = 0.0;
+  fetch(0);
+  for (int t0 = 0; t0 < M; t0 += rows_per_chunk) {
+    const int rows = M - t0 < rows_per_chunk ? M - t0 : rows_per_chunk;
+#pragma unroll
+    for (int u = 0; u < kScoreLoads; ++u) {
+      const int idx = tid + u * nt;
+      if (idx < rows * N) tab[idx] = nxt[u];
+    }
+    __syncthreads();
+    if (t0 + rows_per_chunk < M) fetch(t0 + rows_per_chunk);
+    if (tid < N)
+      for (int r = 0; r < rows; ++r) acc += tab[r * N + tid];
+    __syncthreads();
   }
   return acc;
 }
@@ -108,6 +143,17 @@ __device__ void build_segments(const int32_t *tok_ids, int M, int k, int B, int 
   }
 }
 
+// Bytes of the selection arrays at the start of the budget kernel's LDS (the score staging follows), and the
+// rows of one staging chunk: kBudgetThreads * kScoreLoads values, at most 64 rows.
+__host__ __device__ inline size_t budget_sel_bytes(int N, int k, int B) {
+  const size_t b = sizeof(double) * (2 * (size_t)N + ((k + 1) & ~1) + 2) + sizeof(int32_t) * ((size_t)k + B + 2 * N + 1) + N;
+  return (b + 15) & ~(size_t)15;
+}
+__host__ __device__ inline int budget_rows_per_chunk(int N) {
+  const int r = kBudgetThreads * kScoreLoads / N;
+  return r > 64 ? 64 : (r < 1 ? 1 : r);
+}
+
 // One workgroup per tree token.  Every workgroup recomputes the (tiny) scores and shortlist so that
 // no grid-wide synchronisation is needed; workgroup 0 also writes them out.  The workgroup that
 // finishes last (ticket counter done[0], zero at launch) builds the segments from everybody's rows,
@@ -129,6 +175,8 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
   int32_t *pos = rank + N;                                        // [N] shortlist rank of every expert
   int32_t *flag = pos + N;                                        // [1] "this workgroup is the last one"
   uint8_t *inS = reinterpret_cast<uint8_t *>(flag + 1);           // [N] membership
+  double *tab = reinterpret_cast<double *>(smem + budget_sel_bytes(N, k, B));  // [rows_per_chunk, N] score staging
+  const int rows_per_chunk = budget_rows_per_chunk(N);
 
   const int t = blockIdx.x, tid = threadIdx.x;
 
@@ -140,12 +188,17 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
   if (ext_shortlist == nullptr) {
     // Eq. (5): s_i = sum over the M tree tokens of g_i(h_t), tokens in ascending order.
     // (large trees: summed once by scores_kernel instead of by every workgroup)
-    for (int i = tid; i < N; i += blockDim.x) s[i] = scores_in ? scores_in[i] : column_sum(probs, M, N, i);
+    if (scores_in) {
+      for (int i = tid; i < N; i += blockDim.x) s[i] = scores_in[i];
+    } else {
+      const double acc = column_sums_staged(probs, M, N, rows_per_chunk, tab);
+      if (tid < N) s[tid] = acc;
+    }
     __syncthreads();
     select_topk(s, nullptr, N, B, S, rank);
   } else {
     for (int r = tid; r < B; r += blockDim.x) S[r] = ext_shortlist[r];
-    if (scores && t == 0)
+    if (scores && t == 0)  // uniform in the workgroup
       for (int i = tid; i < N; i += blockDim.x) s[i] = scores_in ? scores_in[i] : column_sum(probs, M, N, i);
   }
   __syncthreads();
@@ -222,12 +275,13 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
                  reinterpret_cast<int32_t *>(smem));
 }
 
-// Eq. (5) once for the whole tree (same order of additions as column_sum): used when the tree is so large
-// that recomputing the scores in every workgroup of budget_kernel would dominate.
-__global__ __launch_bounds__(64) void scores_kernel(const double *__restrict__ probs, int M, int N,
-                                                    double *__restrict__ scores) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < N) scores[i] = column_sum(probs, M, N, i);
+// Eq. (5) once for the whole tree (same order of additions): used when the tree is so large that recomputing
+// the scores in every workgroup of budget_kernel (M^2 N loads in total) would dominate.  One workgroup.
+__global__ __launch_bounds__(kBudgetThreads) void scores_kernel(const double *__restrict__ probs, int M, int N,
+                                                                double *__restrict__ scores) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const double acc = column_sums_staged(probs, M, N, budget_rows_per_chunk(N), reinterpret_cast<double *>(smem));
+  if ((int)threadIdx.x < N) scores[threadIdx.x] = acc;
 }
 
 __global__ void zero_words_kernel(int32_t *p, int n) {
@@ -248,13 +302,14 @@ hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int
   // above this many tokens the redundant per-workgroup scoring (M^2 N loads in total) is replaced by one pass
   const double *scores_in = nullptr;
   if (M > kRedundantScoreTokens && (ext_shortlist == nullptr || scores != nullptr)) {
-    scores_kernel<<<(N + 63) / 64, 64, 0, st>>>(probs, M, N, score_scratch);
+    scores_kernel<<<1, kBudgetThreads, sizeof(double) * budget_rows_per_chunk(N) * N, st>>>(probs, M, N,
+                                                                                           score_scratch);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     scores_in = score_scratch;
   }
   const int staged = (size_t)M * k <= 8192;
-  const size_t smem_sel = sizeof(double) * (2 * N + ((k + 1) & ~1) + 2) + sizeof(int32_t) * (k + B + 2 * N + 1) + N;
+  const size_t smem_sel = budget_sel_bytes(N, k, B) + sizeof(double) * budget_rows_per_chunk(N) * N;
   const size_t smem_seg = sizeof(int32_t) * (3 * B + 1 + (staged ? (size_t)M * k : 0));
   budget_kernel<<<M, kBudgetThreads, smem_sel > smem_seg ? smem_sel : smem_seg, st>>>(
       probs, M, N, k, B, policy, ds.renorm, ext_shortlist, scores, budget_ids, seg_expert, tok_ids, tok_w, seg_off, perm,
