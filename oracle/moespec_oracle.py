@@ -37,6 +37,8 @@ Readings where the paper is silent
   * rankings compare the routing probabilities g (as the paper words it), in fp64;
   * a router bias ``b`` is added to the projection when given (the workloads use
     one to make routing heavy-tailed); ``b=None`` is Eq. (1) as printed;
+  * sigmoid-gated routing (named by the paper as an open case) replaces only the gate: g_i = sigmoid of the
+    logit, and T_k, Eq. (5), Eq. (7)/(8) are applied to those scores unchanged;
   * substitution weights are the full-softmax g_i restricted to the new set,
     renormalised over that set when the architecture renormalises;
   * Eq. (6) writes the partial sum over all j in S + {i} with raw g; it is read as the sum over
@@ -73,13 +75,25 @@ def router_logits(h, w_router, b_router=None) -> np.ndarray:
     return logits
 
 
-def routing_probs(logits) -> np.ndarray:
-    """g[t, :] = softmax over all N experts of logit[t, :] (max-subtracted)."""
+SOFTMAX, SIGMOID = "softmax", "sigmoid"
+
+
+def routing_probs(logits, gate: str = SOFTMAX) -> np.ndarray:
+    """g[t, :] = softmax over all N experts of logit[t, :] (max-subtracted), Eq. (1).
+
+    gate="sigmoid": g[t, i] = 1 / (1 + exp(-logit[t, i])), every expert gated on its own (the routing scheme the
+    paper's limitations section names as an open case; everything downstream - T_k, Eq. (5), Eq. (7)/(8) - is
+    applied to these scores unchanged)."""
     logits = _f64(logits)
     g = np.empty_like(logits)
     for t in range(logits.shape[0]):
-        e = np.exp(logits[t] - np.max(logits[t]))
-        g[t] = e / np.sum(e)
+        if gate == SIGMOID:
+            g[t] = 1.0 / (1.0 + np.exp(-logits[t]))
+        elif gate == SOFTMAX:
+            e = np.exp(logits[t] - np.max(logits[t]))
+            g[t] = e / np.sum(e)
+        else:
+            raise ValueError("unknown gate")
     return g
 
 
@@ -105,9 +119,9 @@ def mixing_weights(g_row, ids: Sequence[int], renorm: bool) -> List[float]:
     return [float(g_row[i]) for i in ids]
 
 
-def route(h, w_router, b_router, k: int, renorm: bool):
+def route(h, w_router, b_router, k: int, renorm: bool, gate: str = SOFTMAX):
     """Unbudgeted routing of every token: (g[M,N], ids[M,k], w[M,k])."""
-    g = routing_probs(router_logits(h, w_router, b_router))
+    g = routing_probs(router_logits(h, w_router, b_router), gate)
     M = g.shape[0]
     ids = np.zeros((M, k), dtype=np.int32)
     w = np.zeros((M, k), dtype=np.float64)
@@ -360,9 +374,10 @@ def budget(g, topk_ids, topk_w, B: int, policy: int, k: int, renorm: bool,
 
 
 def layer_forward(h, weights: Dict[str, np.ndarray], k: int, renorm: bool, B: int, policy: int,
-                  tokens: Optional[Sequence[int]] = None, ext_shortlist: Optional[Sequence[int]] = None):
+                  tokens: Optional[Sequence[int]] = None, ext_shortlist: Optional[Sequence[int]] = None,
+                  gate: str = SOFTMAX):
     """Algorithm 1 end to end for one layer.  Returns a dict of every intermediate and ``out``."""
-    g, topk_ids, topk_w = route(h, weights["w_router"], weights.get("b_router"), k, renorm)
+    g, topk_ids, topk_w = route(h, weights["w_router"], weights.get("b_router"), k, renorm, gate)
     r = budget(g, topk_ids, topk_w, B, policy, k, renorm, ext_shortlist)
     r.update(probs=g, topk_ids=topk_ids, topk_w=topk_w, union=expert_union(topk_ids))
     r["loaded"] = sorted({int(e) for e in r["tok_ids"].ravel() if e >= 0})
@@ -371,9 +386,9 @@ def layer_forward(h, weights: Dict[str, np.ndarray], k: int, renorm: bool, B: in
 
 
 def unbudgeted_forward(h, weights: Dict[str, np.ndarray], k: int, renorm: bool,
-                       tokens: Optional[Sequence[int]] = None) -> np.ndarray:
+                       tokens: Optional[Sequence[int]] = None, gate: str = SOFTMAX) -> np.ndarray:
     """Eq. (2): the standard MoE output over each token's natural top-k."""
-    _, ids, w = route(h, weights["w_router"], weights.get("b_router"), k, renorm)
+    _, ids, w = route(h, weights["w_router"], weights.get("b_router"), k, renorm, gate)
     return combine(h, ids, w, weights["w_gate"], weights["w_up"], weights["w_down"], tokens)
 
 

@@ -357,3 +357,40 @@ def test_decision_margins_small_case():
     assert m["topk"] == pytest.approx(0.1)          # token 1: 0.4, 0.3, 0.2
     assert m["score"] == pytest.approx(0.05)        # scores .6 .5 .45 .45 -> top3 gaps .1, .05
     assert m["sub"] == pytest.approx(0.1)           # token 1 within S: .4 .2 .1 -> .2, .1 ; token 0: .5 .3 .05 -> .2, .25
+
+
+# ------------------------------------------------------------------------------------- sigmoid gate
+def test_sigmoid_gate_matches_library_sigmoid_and_keeps_the_selection():
+    import torch
+    rng = np.random.default_rng(12)
+    logits = rng.standard_normal((9, 7)) * 3.0
+    g = O.routing_probs(logits, O.SIGMOID)
+    np.testing.assert_allclose(g, torch.sigmoid(torch.from_numpy(logits)).numpy(), rtol=1e-14)
+    assert np.all((g > 0) & (g < 1)) and not np.allclose(g.sum(axis=1), 1.0)     # no normalisation across experts
+    # both gates are increasing in the logit: the natural top-k sets and their order are the same
+    gs = O.routing_probs(logits, O.SOFTMAX)
+    for t in range(9):
+        assert O.top_k(g[t], 3) == O.top_k(gs[t], 3) == list(np.argsort(-logits[t], kind="stable")[:3])
+    # renormalised mixing weights: sigmoid scores over their sum
+    sel = O.top_k(g[0], 3)
+    w = O.mixing_weights(g[0], sel, True)
+    np.testing.assert_allclose(w, g[0][sel] / g[0][sel].sum(), rtol=1e-15)
+    with pytest.raises(ValueError):
+        O.routing_probs(logits, "tanh")
+
+
+def test_sigmoid_gate_changes_the_aggregate_ranking_but_not_the_full_budget_layer():
+    rng = np.random.default_rng(13)
+    M, d, N, k, F = 14, 8, 6, 2, 4
+    W = dict(w_router=rng.standard_normal((N, d)), b_router=None, w_gate=rng.standard_normal((N, F, d)) * 0.3,
+             w_up=rng.standard_normal((N, F, d)) * 0.3, w_down=rng.standard_normal((N, d, F)) * 0.3)
+    h = rng.standard_normal((M, d))
+    full = O.unbudgeted_forward(h, W, k, True, gate=O.SIGMOID)
+    r = O.layer_forward(h, W, k, True, N, O.SUBSTITUTE, gate=O.SIGMOID)
+    np.testing.assert_allclose(r["out"], full, rtol=1e-13, atol=1e-15)
+    # Eq. (5) on sigmoid scores: the column sums of the gate values
+    np.testing.assert_allclose(r["scores"], O.routing_probs(O.router_logits(h, W["w_router"]), O.SIGMOID).sum(axis=0),
+                               rtol=1e-13)
+    # one hot logit far above the rest: softmax gives it all the mass, sigmoid leaves the others near 1/2
+    z = np.array([[20.0, 0.1, 0.0, -0.1]])
+    assert O.routing_probs(z, O.SOFTMAX)[0, 1] < 1e-8 and abs(O.routing_probs(z, O.SIGMOID)[0, 1] - 0.525) < 1e-3
