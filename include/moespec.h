@@ -64,6 +64,11 @@ typedef enum { MOESPEC_F32 = 0, MOESPEC_BF16 = 1 } moespec_dtype;
 /* Coverage policy of Section 3.3: Eq. (7) truncation or Eq. (8) substitution. */
 typedef enum { MOESPEC_TRUNCATE = 0, MOESPEC_SUBSTITUTE = 1 } moespec_policy;
 
+/* Gate of the router: the softmax over all experts of Eq. (1), or an independent sigmoid per expert
+ * (the routing scheme the paper's limitations section names as an open case; T_k, Eq. (5) and
+ * Eq. (7)/(8) are applied to the sigmoid scores unchanged). */
+typedef enum { MOESPEC_GATE_SOFTMAX = 0, MOESPEC_GATE_SIGMOID = 1 } moespec_gate;
+
 /* Shape of one MoE layer.  Host struct. */
 typedef struct {
   int32_t d;         /* hidden size                                                         */
@@ -73,6 +78,7 @@ typedef struct {
   int32_t dtype;     /* moespec_dtype: storage of h, the weights, residual and out          */
   int32_t renorm;    /* 0: mixing weights are the raw g_i; 1: g_i / sum over the selected   */
                      /* set (Section 2.1: "depending on the architecture")                  */
+  int32_t gate;      /* moespec_gate                                                        */
 } moespec_desc;
 
 /* Weights of one MoE layer.  Host struct holding device pointers. */
@@ -93,7 +99,7 @@ const char *moespec_status_string(int32_t status);
 /*
  * Checks that the kernels cover this layer shape: d and d_ff multiples of 32 (bf16) or 4 (f32),
  * d <= 8192, d_ff <= 2^20, 1 <= top_k <= n_experts <= 1024, top_k <= 64, n_experts * d_ff * d < 2^40, dtype and
- * renorm valid.
+ * renorm and gate valid.
  * Returns MOESPEC_OK, MOESPEC_ERR_INVALID_ARG or MOESPEC_ERR_UNSUPPORTED_SHAPE.  Host only.
  */
 moespec_status moespec_check_desc(const moespec_desc *desc);

@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libmoespec.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = range(5)
 F32, BF16 = 0, 1
 TRUNCATE, SUBSTITUTE = 0, 1
+GATE_SOFTMAX, GATE_SIGMOID = 0, 1
 
 EXPORTS = ("moespec_abi_version", "moespec_status_string", "moespec_check_desc", "moespec_workspace_bytes",
            "moespec_route", "moespec_budget", "moespec_expert_ffn", "moespec_layer_forward",
@@ -36,7 +37,7 @@ class MoeSpecError(RuntimeError):
 
 class Desc(Structure):
     _fields_ = [("d", c_int32), ("n_experts", c_int32), ("top_k", c_int32), ("d_ff", c_int32),
-                ("dtype", c_int32), ("renorm", c_int32)]
+                ("dtype", c_int32), ("renorm", c_int32), ("gate", c_int32)]
 
 
 class Weights(Structure):
@@ -122,9 +123,10 @@ class LayerDesc:
     d_ff: int
     dtype: int          # F32 or BF16
     renorm: bool
+    gate: int = 0       # GATE_SOFTMAX or GATE_SIGMOID
 
     def c(self) -> Desc:
-        return Desc(self.d, self.n_experts, self.top_k, self.d_ff, self.dtype, int(self.renorm))
+        return Desc(self.d, self.n_experts, self.top_k, self.d_ff, self.dtype, int(self.renorm), int(self.gate))
 
     @property
     def torch_dtype(self) -> torch.dtype:

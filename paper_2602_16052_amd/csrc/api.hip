@@ -18,6 +18,7 @@ moespec_status check_desc(const moespec_desc *ds) {
   if (!ds) return MOESPEC_ERR_INVALID_ARG;
   if (ds->dtype != MOESPEC_F32 && ds->dtype != MOESPEC_BF16) return MOESPEC_ERR_INVALID_ARG;
   if (ds->renorm != 0 && ds->renorm != 1) return MOESPEC_ERR_INVALID_ARG;
+  if (ds->gate != MOESPEC_GATE_SOFTMAX && ds->gate != MOESPEC_GATE_SIGMOID) return MOESPEC_ERR_INVALID_ARG;
   if (ds->d < 1 || ds->d_ff < 1 || ds->n_experts < 1) return MOESPEC_ERR_INVALID_ARG;
   if (ds->top_k < 1 || ds->top_k > ds->n_experts) return MOESPEC_ERR_INVALID_ARG;
   if (ds->n_experts > kMaxExperts || ds->top_k > kMaxTopK || ds->d > kMaxHidden || ds->d_ff > kMaxInter)
@@ -62,7 +63,7 @@ moespec_status from_hip(hipError_t e) { return e == hipSuccess ? MOESPEC_OK : MO
 
 extern "C" {
 
-int32_t moespec_abi_version(void) { return 1; }
+int32_t moespec_abi_version(void) { return 2; }
 
 const char *moespec_status_string(int32_t status) {
   switch (status) {

@@ -66,10 +66,11 @@ __global__ __launch_bounds__(kLogitThreads) void logits_kernel(const T *__restri
   }
 }
 
-// probs[t, :] = softmax(logits[t, :]) in place (max-subtracted), then the natural top-k and its mixing
-// weights if asked for.  One workgroup per token.
+// probs[t, :] = softmax(logits[t, :]) in place (max-subtracted) - or, with the sigmoid gate, 1 / (1 + exp(-logit))
+// per expert - then the natural top-k and its mixing weights if asked for.  One workgroup per token.
 __global__ __launch_bounds__(kSoftmaxThreads) void softmax_topk_kernel(double *__restrict__ probs, int N, int k,
-                                                                       int renorm, int32_t *__restrict__ topk_ids,
+                                                                       int renorm, int sigmoid_gate,
+                                                                       int32_t *__restrict__ topk_ids,
                                                                        float *__restrict__ topk_w,
                                                                        int32_t *__restrict__ zero_words, int n_zero) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -83,34 +84,43 @@ __global__ __launch_bounds__(kSoftmaxThreads) void softmax_topk_kernel(double *_
     for (int i = tid; i < n_zero; i += blockDim.x) zero_words[i] = 0;
   for (int i = tid; i < N; i += blockDim.x) g[i] = probs[(size_t)t * N + i];
   __syncthreads();
-  // 32 strided partial results, then every thread folds the 32 in index order
-  if (tid < 32) {
-    double m = -INFINITY;
-    for (int i = tid; i < N; i += 32) m = fmax(m, g[i]);
-    part[tid] = m;
+  if (sigmoid_gate) {  // uniform
+    for (int i = tid; i < N; i += blockDim.x) {
+      const double p = 1.0 / (1.0 + exp(-g[i]));
+      g[i] = p;
+      probs[(size_t)t * N + i] = p;
+    }
+    __syncthreads();
+  } else {
+    // 32 strided partial results, then every thread folds the 32 in index order
+    if (tid < 32) {
+      double m = -INFINITY;
+      for (int i = tid; i < N; i += 32) m = fmax(m, g[i]);
+      part[tid] = m;
+    }
+    __syncthreads();
+    double m = part[0];
+  #pragma unroll
+    for (int j = 1; j < 32; ++j) m = fmax(m, part[j]);
+    __syncthreads();
+    for (int i = tid; i < N; i += blockDim.x) g[i] = exp(g[i] - m);
+    __syncthreads();
+    if (tid < 32) {
+      double a = 0.0;
+      for (int i = tid; i < N; i += 32) a += g[i];
+      part[tid] = a;
+    }
+    __syncthreads();
+    double denom = part[0];
+  #pragma unroll
+    for (int j = 1; j < 32; ++j) denom += part[j];
+    for (int i = tid; i < N; i += blockDim.x) {
+      const double p = g[i] / denom;
+      g[i] = p;
+      probs[(size_t)t * N + i] = p;
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  double m = part[0];
-#pragma unroll
-  for (int j = 1; j < 32; ++j) m = fmax(m, part[j]);
-  __syncthreads();
-  for (int i = tid; i < N; i += blockDim.x) g[i] = exp(g[i] - m);
-  __syncthreads();
-  if (tid < 32) {
-    double a = 0.0;
-    for (int i = tid; i < N; i += 32) a += g[i];
-    part[tid] = a;
-  }
-  __syncthreads();
-  double denom = part[0];
-#pragma unroll
-  for (int j = 1; j < 32; ++j) denom += part[j];
-  for (int i = tid; i < N; i += blockDim.x) {
-    const double p = g[i] / denom;
-    g[i] = p;
-    probs[(size_t)t * N + i] = p;
-  }
-  __syncthreads();
 
   if (topk_ids == nullptr && topk_w == nullptr) return;
   select_topk(g, nullptr, N, k, sel, rank);
@@ -140,7 +150,8 @@ hipError_t launch_route(const moespec_desc &ds, const moespec_weights &wt, const
   if (e != hipSuccess) return e;
   const size_t smem = sizeof(double) * (((N + 1) & ~1) + 32 + ((k + 1) & ~1) + 2) +
                       sizeof(int32_t) * (((k + 3) & ~3) + N);
-  softmax_topk_kernel<<<M, kSoftmaxThreads, smem, st>>>(probs, N, k, ds.renorm, topk_ids, topk_w, zero_words,
+  softmax_topk_kernel<<<M, kSoftmaxThreads, smem, st>>>(probs, N, k, ds.renorm, ds.gate == MOESPEC_GATE_SIGMOID ? 1 : 0,
+                                                        topk_ids, topk_w, zero_words,
                                                         n_zero);
   return hipGetLastError();
 }

@@ -52,6 +52,7 @@ class LayerConfig:
     n_layers: int = 1
     seed: int = 0
     sigma_w: float = 0.02
+    gate: str = "softmax"  # "softmax" (Eq. (1)) or "sigmoid" (independent gate per expert)
 
     @property
     def elem_bytes(self) -> int:
@@ -172,7 +173,7 @@ def layer_weights(cfg: LayerConfig, layer: int = 0, seed: Optional[int] = None,
 
 def small_config(name: str = "small", dtype: str = "bf16", d: int = 256, n_experts: int = 16, top_k: int = 4,
                  d_ff: int = 192, M: int = 37, budgets: Tuple[int, ...] = (8,), bias_alpha: float = 1.5,
-                 renorm: bool = True, seed: int = 0, n_layers: int = 1) -> LayerConfig:
+                 renorm: bool = True, seed: int = 0, n_layers: int = 1, gate: str = "softmax") -> LayerConfig:
     """A free-form config for randomised parity cases (ragged sizes, edge shapes)."""
     return LayerConfig(name, dtype, d, n_experts, top_k, d_ff, M, tuple(budgets), bias_alpha, renorm,
-                       n_layers=n_layers, seed=seed)
+                       n_layers=n_layers, seed=seed, gate=gate)

@@ -12,7 +12,7 @@ TOL = {"bf16": 2e-2, "f32": 1e-5}
 
 def desc_of(cfg) -> mb.LayerDesc:
     return mb.LayerDesc(cfg.d, cfg.n_experts, cfg.top_k, cfg.d_ff, mb.BF16 if cfg.dtype == "bf16" else mb.F32,
-                        cfg.renorm)
+                        cfg.renorm, mb.GATE_SIGMOID if cfg.gate == "sigmoid" else mb.GATE_SOFTMAX)
 
 
 def to_device(x: np.ndarray) -> torch.Tensor:

@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert mb.abi_version() == 1
+    assert mb.abi_version() == 2
     assert mb.status_string(mb.OK) == "ok"
     assert "workspace" in mb.status_string(mb.ERR_WORKSPACE_TOO_SMALL)
     assert mb.status_string(99) == "unknown status"
@@ -48,6 +48,8 @@ def D(**kw):
 def test_check_desc_and_workspace(lib):
     assert mb.check_desc(D()) == mb.OK
     assert mb.check_desc(D(dtype=7)) == mb.ERR_INVALID_ARG
+    assert mb.check_desc(D(gate=mb.GATE_SIGMOID)) == mb.OK
+    assert mb.check_desc(D(gate=2)) == mb.ERR_INVALID_ARG
     assert mb.check_desc(D(top_k=0)) == mb.ERR_INVALID_ARG
     assert mb.check_desc(D(top_k=17)) == mb.ERR_INVALID_ARG
     assert mb.check_desc(D(d=0)) == mb.ERR_INVALID_ARG

@@ -43,6 +43,11 @@ SMALL = {
     # the largest expert count and top-k the descriptor check admits
     "s_bf16_n1024": wl.small_config("s_bf16_n1024", "bf16", d=64, n_experts=1024, top_k=64, d_ff=32, M=9,
                                     budgets=(64, 300, 1024), bias_alpha=0.7),
+    # sigmoid-gated routing (an independent gate per expert instead of the softmax of Eq. (1))
+    "s_bf16_sigmoid": wl.small_config("s_bf16_sigmoid", "bf16", d=256, n_experts=16, top_k=4, d_ff=128, M=45,
+                                      budgets=(4, 9, 16), bias_alpha=0.8, gate="sigmoid"),
+    "s_f32_sigmoid": wl.small_config("s_f32_sigmoid", "f32", d=100, n_experts=12, top_k=3, d_ff=52, M=19,
+                                     budgets=(3, 6, 12), renorm=False, gate="sigmoid"),
     "s_f32_a": wl.small_config("s_f32_a", "f32", d=100, n_experts=12, top_k=3, d_ff=52, M=19, budgets=(3, 6, 12)),
     "tiny_f32": wl.CONFIGS["tiny_f32"],
 }
@@ -75,7 +80,7 @@ def test_route_parity(cases, name):
     cfg = c["cfg"]
     r = mb.moespec_route(c["desc"], c["W_d"], c["h_d"], c["ws"])
     torch.cuda.synchronize()
-    g, ids, w = O.route(c["h_o"], c["W_o"]["w_router"], c["W_o"]["b_router"], cfg.top_k, cfg.renorm)
+    g, ids, w = O.route(c["h_o"], c["W_o"]["w_router"], c["W_o"]["b_router"], cfg.top_k, cfg.renorm, cfg.gate)
     np.testing.assert_allclose(r["probs"].cpu().numpy(), g, rtol=1e-11, atol=1e-300)
     assert np.array_equal(r["topk_ids"].cpu().numpy(), ids)
     np.testing.assert_allclose(r["topk_w"].cpu().numpy(), w, rtol=1e-6)
@@ -92,7 +97,7 @@ def test_layer_forward_parity_small(cases, name, policy):
         print(f"case {name} B={B} policy={policy}", flush=True)
         out, taps = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], B, policy, c["ws"], taps=True)
         torch.cuda.synchronize()
-        ref = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, B, policy)
+        ref = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, B, policy, gate=cfg.gate)
         assert_routing_equal(taps, ref, B)
         assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)
         # without taps the budget stage may skip the grouping of the pairs: same output, bit for bit

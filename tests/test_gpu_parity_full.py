@@ -4,6 +4,7 @@ Routing (shortlist, per-token ids, segments, permutation) is compared with the o
 token, bit-exact.  Layer outputs are compared on sampled tokens, which the oracle computes one by
 one (a full fp64 layer on the host would take minutes); all other rows are checked for finiteness
 and, under truncation, dropped tokens for exact zeros."""
+import dataclasses
 import time
 
 import numpy as np
@@ -21,15 +22,21 @@ pytestmark = pytest.mark.gpu
 
 
 def routing_reference(cfg, h_o, W_o, B, policy):
-    g, ids, w = O.route(h_o, W_o["w_router"], W_o["b_router"], cfg.top_k, cfg.renorm)
+    g, ids, w = O.route(h_o, W_o["w_router"], W_o["b_router"], cfg.top_k, cfg.renorm, cfg.gate)
     r = O.budget(g, ids, w, B, policy, cfg.top_k, cfg.renorm)
     r.update(probs=g, loaded=sorted({int(e) for e in r["tok_ids"].ravel() if e >= 0}), union=O.expert_union(ids))
     return r
 
 
-@pytest.fixture(scope="module", params=["olmoe_m63", "olmoe_m127", "fine_m127"])
+# a second routing scheme at full size: the OLMoE-shaped layer with a sigmoid gate per expert
+FULL = dict(wl.CONFIGS)
+FULL["olmoe_m63_sigmoid"] = dataclasses.replace(wl.CONFIGS["olmoe_m63"], name="olmoe_m63_sigmoid", gate="sigmoid",
+                                                budgets=(16, 32, 64))
+
+
+@pytest.fixture(scope="module", params=["olmoe_m63", "olmoe_m127", "fine_m127", "olmoe_m63_sigmoid"])
 def full_case(request):
-    cfg = wl.CONFIGS[request.param]
+    cfg = FULL[request.param]
     t0 = time.time()
     W = wl.layer_weights(cfg, threads=16)
     h = wl.hidden_states(cfg)
