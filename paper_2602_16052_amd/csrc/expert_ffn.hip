@@ -12,8 +12,8 @@
 // of one expert and walks K in chunks; however uneven the segment sizes, every compute unit
 // streams the same number of weight bytes.  Per chunk each wave loads its rows with fully
 // coalesced 16-byte loads, parks them in a wave-private, XOR-swizzled LDS tile and reads them
-// back in MFMA operand layout; the token chunk is loaded once per workgroup into a shared,
-// double-buffered LDS tile.  (Loading operands from global memory directly in MFMA layout costs a
+// back in MFMA operand layout; the token chunk is loaded once per workgroup into a shared LDS
+// tile (double-buffered up to 4 token tiles; one 32 KB buffer and a second barrier for 8).  (Loading operands from global memory directly in MFMA layout costs a
 // cache-line lookup per lane and saturates the texture-address path long before HBM.)
 // Workgroups start their K walk at staggered offsets: weight rows are a power-of-two stride
 // apart, and equal offsets would pile the concurrent reads onto the same memory channels.
@@ -291,7 +291,7 @@ struct Chunk {
 
 // The wave index is taken through readfirstlane in these kernels: it is uniform within a wave, and the
 // compiler then keeps everything derived from it (row offsets, tile bases) in scalar registers.
-constexpr int kLdsBytes = 65536;  // 32 KB of wave-private weight tiles + 2 x 16 KB token tile (or 16 + 2 x 16)
+constexpr int kLdsBytes = 65536;  // 32 KB of wave-private weight tiles + token tile: 2 x (4..16) KB or 1 x 32 KB
 
 // One workgroup pass over K for NT token tiles.  wt0 / wt1: first row of this wave's two 16-row weight
 // tiles (row stride K elements).  xbase + xsrc[q] bytes: this lane's source row (already at its 16-byte piece)
