@@ -121,7 +121,7 @@ moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weight
   if (!aligned16(h) || !aligned16(out) || (residual && !aligned16(residual))) return MOESPEC_ERR_INVALID_ARG;
   Workspace w = carve_workspace(*desc, M, ws);
   return from_hip(launch_expert_ffn(*desc, *weights, h, M, n_seg, seg_expert, seg_off, perm, tok_ids, tok_w, residual,
-                                    out, w.act, w.y, w.items, false, nullptr, nullptr,
+                                    out, w.act, w.y, w.items, false, nullptr, nullptr, nullptr, nullptr,
                                     static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -163,8 +163,8 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(2);
   e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
-                        w.y, w.items, want_segments, self_seg ? w.done + 1 : nullptr, budget_ids, st,
-                        tr ? tr + 3 : nullptr);
+                        w.y, w.items, want_segments, self_seg ? w.done + 1 : nullptr, budget_ids, w.pub_items,
+                        w.pub_lists, st, tr ? tr + 3 : nullptr);
   return from_hip(e);
 }
 
@@ -225,7 +225,8 @@ moespec_status moespec_oracle_ranking(const moespec_desc *desc, const moespec_we
                     w.seg_expert, w.seg_off, w.perm, nullptr, w.items, w.done, true, !self_seg, w.scores, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   e = launch_expert_ffn(*desc, *weights, h, M, N, w.seg_expert, w.seg_off, w.perm, w.tok_ids, w.tok_w, nullptr,
-                        nullptr, w.act, w.y, w.items, !self_seg, self_seg ? w.done + 1 : nullptr, w.budget_ids, st);
+                        nullptr, w.act, w.y, w.items, !self_seg, self_seg ? w.done + 1 : nullptr, w.budget_ids,
+                        w.pub_items, w.pub_lists, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   return from_hip(launch_oracle_ranking(*desc, w.y, down_splits(*desc, N), (size_t)M * desc->top_k * desc->d,
                                         w.tok_ids, w.tok_w, M, B, static_cast<double *>(w.act), w.gram, ranking, err,

@@ -122,6 +122,8 @@ struct Workspace {
   int32_t *seg_off;   // [N + 1]
   int32_t *perm;      // [M * k]
   int4 *items;        // [N + 1] count, then (segment, expert, offset, size) of the non-empty segments
+  int4 *pub_items;    // [N + 1] the same table as published by a self-segmenting gate/up pass
+  int32_t *pub_lists; // [min(N, 256), min(M, 1024)] its pair lists
   int32_t *n_loaded;  // [1]
   int32_t *done;      // [1 + N] ticket counter of the budget stage, then surviving pairs per shortlist rank
   void *act;          // [M * k, F] dtype
@@ -150,6 +152,8 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
   w.seg_off = static_cast<int32_t *>(take(sizeof(int32_t) * (N + 1)));
   w.perm = static_cast<int32_t *>(take(sizeof(int32_t) * M * k));
   w.items = static_cast<int4 *>(take(sizeof(int4) * (N + 1)));
+  w.pub_items = static_cast<int4 *>(take(sizeof(int4) * (N + 1)));
+  w.pub_lists = static_cast<int32_t *>(take(sizeof(int32_t) * (N < 256 ? N : 256) * (M < 1024 ? M : 1024)));
   w.n_loaded = static_cast<int32_t *>(take(sizeof(int32_t)));
   w.done = static_cast<int32_t *>(take(sizeof(int32_t) * (1 + N)));
   w.act = take(es * M * k * F);
@@ -177,13 +181,15 @@ hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int
 // rank_count, shortlist (may be NULL): the shortlist in rank order ([n_seg]) and the surviving pairs of each
 // of its experts, from the budget stage; when given and the shape allows (expert_ffn_self_segmenting),
 // every workgroup derives its segment from them and tok_ids itself, and seg_expert / seg_off / perm /
-// items are not read.
+// items are not read.  pub_items ([n_seg + 1] int4) and pub_lists ([n_seg, M] int32) are scratch in which the gate/up pass
+// of that mode leaves its segments for the down pass (NULL: the down pass derives them again).
 // trace (may be NULL): 3 events recorded after the gate/up pass, the down pass and the combine.
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
                              float *y, int4 *items, bool items_ready, const int32_t *rank_count,
-                             const int32_t *shortlist, hipStream_t st, void *const *trace = nullptr);
+                             const int32_t *shortlist, int4 *pub_items, int32_t *pub_lists, hipStream_t st,
+                             void *const *trace = nullptr);
 bool expert_ffn_self_segmenting(const moespec_desc &ds, int M);
 // Number of K-split copies of y that launch_expert_ffn writes for n_seg segments; out == NULL there skips
 // the combine and leaves the per-pair expert outputs in y.

@@ -34,8 +34,8 @@ constexpr int kMaxTiles = 8;  // token tiles of 16 per pass over the weights
 
 // A segment is processed only if it names a real expert and lies inside the pair table; pair
 // indices are clamped into [0, M*k) so that malformed tables cannot address outside the buffers.
-__device__ __forceinline__ bool segment_ok(int e, int beg, int m, int M, int N, int k) {
-  return e >= 0 && e < N && m > 0 && beg >= 0 && (long long)beg + m <= (long long)M * k;
+__device__ __forceinline__ bool segment_ok(int e, int beg, int m, long long list_len, int N) {
+  return e >= 0 && e < N && m > 0 && beg >= 0 && (long long)beg + m <= list_len;
 }
 __device__ __forceinline__ int pair_index(const int32_t *perm, int pos, int M, int k) {
   const int q = perm[pos];
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_bf16_kernel(
   const int seg = blockIdx.y;
   const int e = seg_expert[seg];
   const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
-  if (!segment_ok(e, beg, m, M, N, k)) return;
+  if (!segment_ok(e, beg, m, (long long)M * k, N)) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int f0 = (blockIdx.x * kFfnWaves + wave) * 16;
   if (f0 >= F) return;
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_bf16_kernel(
   const int seg = blockIdx.y;
   const int e = seg_expert[seg];
   const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
-  if (!segment_ok(e, beg, m, M, N, k)) return;
+  if (!segment_ok(e, beg, m, (long long)M * k, N)) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int j0 = (blockIdx.x * kFfnWaves + wave) * 32;
   if (j0 >= d) return;
@@ -378,13 +378,15 @@ __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt
 // workgroup takes the shortlisted expert with pairs that xcd_map assigns to it and collects its pairs in token order
 // into plist (LDS, up to M entries).  Everything is read in one round of independent loads.
 // Requires B <= kFfnThreads, k <= kSelfMaxK, M <= kSelfMaxTokens.  misc: 8 int32 of LDS scratch.
-// Called by every thread of the workgroup (it synchronises).  Returns the expert (-1: no such rank).
+// Called by every thread of the workgroup (it synchronises).  Returns the expert (-1: no such rank) and the
+// number of shortlisted experts that have pairs.
 constexpr int kSelfMaxTokens = 1024;  // plist entries
 constexpr int kSelfMaxK = 16;
 __device__ __forceinline__ int self_segment(const int32_t *__restrict__ rank_count,
                                             const int32_t *__restrict__ shortlist, int B,
                                             const int32_t *__restrict__ tok_ids, int M, int k, int tiles,
-                                            int32_t *misc, int32_t *plist, int &m, int &rank, int &tile) {
+                                            int32_t *misc, int32_t *plist, int &m, int &rank, int &tile,
+                                            int &n_nonempty) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int ids[kSelfMaxK];
   auto load_ids = [&](int t) {
@@ -399,7 +401,8 @@ __device__ __forceinline__ int self_segment(const int32_t *__restrict__ rank_cou
   if (lane == 0) misc[1 + wave] = __popcll(mask);
   if (tid == 0) misc[0] = -1;
   __syncthreads();
-  int before = 0, n_nonempty = 0;
+  int before = 0;
+  n_nonempty = 0;
   for (int w = 0; w < kFfnWaves; ++w) {
     if (w < wave) before += misc[1 + w];
     n_nonempty += misc[1 + w];
@@ -478,7 +481,8 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
     const uint16_t *__restrict__ h, const uint16_t *__restrict__ w_gate, const uint16_t *__restrict__ w_up,
     const int4 *__restrict__ items, const int32_t *__restrict__ perm, const int32_t *__restrict__ rank_count,
     const int32_t *__restrict__ shortlist, const int32_t *__restrict__ tok_ids, int n_seg, int M, int N, int k, int d,
-    int F, uint16_t *__restrict__ act) {
+    int F, long long perm_len, int4 *__restrict__ pub_items, int32_t *__restrict__ pub_lists,
+    uint16_t *__restrict__ act) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
   __shared__ int32_t own_pairs[kSelfMaxTokens];
   __shared__ int32_t misc[8];
@@ -486,14 +490,22 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
   int tile, rank, e, m;
   const int32_t *plist;
   if (rank_count) {
-    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile);
+    int n_nonempty;
+    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_nonempty);
+    // The segments found here are published for the down pass (same table format as the budget stage's):
+    // workgroup 0 writes the count, the first row tile of every segment its entry and its pair list (M slots per rank).
+    if (pub_items && blockIdx.x == 0 && threadIdx.x == 0) pub_items[0] = int4{n_nonempty, 0, 0, 0};
     if (e < 0 || e >= N || m <= 0) return;
+    if (pub_items && tile == 0) {
+      for (int p = threadIdx.x; p < m; p += kFfnThreads) pub_lists[(size_t)rank * M + p] = own_pairs[p];
+      if (threadIdx.x == 0) pub_items[1 + rank] = int4{rank, e, rank * M, m};
+    }
     plist = own_pairs;
   } else {
     const int4 it = xcd_item(tiles, n_seg, items, tile, rank);
     e = it.y;
     m = it.w;
-    if (it.x < 0 || !segment_ok(e, it.z, m, M, N, k)) return;
+    if (it.x < 0 || !segment_ok(e, it.z, m, perm_len, N)) return;
     plist = perm + it.z;
   }
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -549,7 +561,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
     const uint16_t *__restrict__ act, const uint16_t *__restrict__ w_down, const int4 *__restrict__ items,
     const int32_t *__restrict__ perm, const int32_t *__restrict__ rank_count, const int32_t *__restrict__ shortlist,
     const int32_t *__restrict__ tok_ids, int n_seg, int M, int N, int k, int d, int F, int splits,
-    float *__restrict__ y) {
+    long long perm_len, float *__restrict__ y) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
   __shared__ int32_t own_pairs[kSelfMaxTokens];
   __shared__ int32_t misc[8];
@@ -559,14 +571,15 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
   int tile, rank, e, m;
   const int32_t *plist;
   if (rank_count) {
-    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile);
+    int n_nonempty;
+    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_nonempty);
     if (e < 0 || e >= N || m <= 0) return;
     plist = own_pairs;
   } else {
     const int4 it = xcd_item(tiles, n_seg, items, tile, rank);
     e = it.y;
     m = it.w;
-    if (it.x < 0 || !segment_ok(e, it.z, m, M, N, k)) return;
+    if (it.x < 0 || !segment_ok(e, it.z, m, perm_len, N)) return;
     plist = perm + it.z;
   }
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -598,7 +611,7 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_gateup_f32_kernel(
   const int seg = blockIdx.y;
   const int e = seg_expert[seg];
   const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
-  if (!segment_ok(e, beg, m, M, N, k)) return;
+  if (!segment_ok(e, beg, m, (long long)M * k, N)) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int f = blockIdx.x * kFfnWaves + wave;
   if (f >= F) return;
@@ -625,7 +638,7 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_down_f32_kernel(
   const int seg = blockIdx.y;
   const int e = seg_expert[seg];
   const int beg = seg_off[seg], m = seg_off[seg + 1] - beg;
-  if (!segment_ok(e, beg, m, M, N, k)) return;
+  if (!segment_ok(e, beg, m, (long long)M * k, N)) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int j = blockIdx.x * kFfnWaves + wave;
   if (j >= d) return;
@@ -738,7 +751,8 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
                              float *y, int4 *items, bool items_ready, const int32_t *rank_count,
-                             const int32_t *shortlist, hipStream_t st, void *const *trace) {
+                             const int32_t *shortlist, int4 *pub_items, int32_t *pub_lists, hipStream_t st,
+                             void *const *trace) {
   const int d = ds.d, F = ds.d_ff, k = ds.top_k;
   hipError_t e;
   if (rank_count && !(shortlist && expert_ffn_self_segmenting(ds, M) && n_seg <= kFfnThreads)) rank_count = nullptr;
@@ -751,6 +765,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
     if (trace && trace[i]) (void)hipEventRecord(static_cast<hipEvent_t>(trace[i]), st);
   };
   const int splits = down_splits(ds, n_seg);
+  const bool publish = rank_count && pub_items && pub_lists;
   const size_t split_stride = (size_t)M * k * d;
   if (ds.dtype == MOESPEC_BF16) {
     for (int pass = 1; pass <= 2; ++pass) {
@@ -760,13 +775,15 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
           ffn_gateup_lds_kernel<<<grid, kFfnThreads, 0, st>>>(
               static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(wt.w_gate),
               static_cast<const uint16_t *>(wt.w_up), items, perm, rank_count, shortlist, tok_ids, n_seg, M,
-              ds.n_experts, k, d, F, static_cast<uint16_t *>(act));
+              ds.n_experts, k, d, F, (long long)M * k, publish ? pub_items : nullptr, pub_lists,
+              static_cast<uint16_t *>(act));
         } else {
           const int grid = xcd_grid(((d / 32 + kFfnWaves - 1) / kFfnWaves) * splits, n_seg);
-          ffn_down_lds_kernel<<<grid, kFfnThreads, 0, st>>>(static_cast<const uint16_t *>(act),
-                                                            static_cast<const uint16_t *>(wt.w_down), items, perm,
-                                                            rank_count, shortlist, tok_ids, n_seg, M, ds.n_experts,
-                                                            k, d, F, splits, y);
+          // after a self-segmenting gate/up pass the down pass reads the segments that pass has published
+          ffn_down_lds_kernel<<<grid, kFfnThreads, 0, st>>>(
+              static_cast<const uint16_t *>(act), static_cast<const uint16_t *>(wt.w_down),
+              publish ? pub_items : items, publish ? pub_lists : perm, publish ? nullptr : rank_count, shortlist,
+              tok_ids, n_seg, M, ds.n_experts, k, d, F, splits, publish ? (long long)n_seg * M : (long long)M * k, y);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         mark(pass - 1);
