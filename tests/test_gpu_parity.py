@@ -200,3 +200,43 @@ def test_ties_go_to_the_lowest_id_on_the_gpu():
         ref = O.layer_forward(wl.as_f32(h), oracle_weights(W), cfg.top_k, cfg.renorm, 4, policy)
         assert_routing_equal(taps, ref, 4)
         assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)
+
+
+def test_shortlist_that_nobody_routes_to_gives_exact_zeros_or_the_residual(cases):
+    """Eq. (7) with an empty intersection for every token: no expert is loaded, the MoE output is exactly zero and
+    only the residual passes through."""
+    c = cases("s_bf16_self")
+    cfg = c["cfg"]
+    _, ids, _ = O.route(c["h_o"], c["W_o"]["w_router"], c["W_o"]["b_router"], cfg.top_k, cfg.renorm)
+    unused = sorted(set(range(cfg.n_experts)) - set(O.expert_union(ids)))
+    assert len(unused) >= 2, "the case needs experts outside the union"
+    ext = torch.tensor(unused[:2], dtype=torch.int32, device="cuda")
+    resid = torch.randn(cfg.M, cfg.d, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
+    out, taps = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], 2, mb.TRUNCATE, c["ws"], ext_shortlist=ext,
+                                         taps=True)
+    plain = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], 2, mb.TRUNCATE, c["ws"], ext_shortlist=ext)
+    with_res = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], 2, mb.TRUNCATE, c["ws"], ext_shortlist=ext,
+                                        residual=resid)
+    torch.cuda.synchronize()
+    assert int(taps["n_loaded"][0]) == 0 and torch.all(taps["tok_ids"] == -1) and torch.all(taps["tok_w"] == 0)
+    assert torch.all(taps["seg_off"][:3] == 0) and torch.all(taps["perm"] == -1)
+    assert torch.all(out == 0) and torch.all(plain == 0) and torch.equal(with_res, resid)
+
+
+def test_external_shortlist_with_repeated_and_invalid_ids(cases):
+    """An external shortlist may repeat an expert or name ids outside [0, N): those entries are ignored, the rest
+    behaves like the clean list (truncation keeps T_k intersected with the set, whatever B says)."""
+    c = cases("s_bf16_a")
+    cfg = c["cfg"]
+    messy = [3, 3, 7, 99, -5, 1]
+    clean = [3, 7, 1]
+    out, taps = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], len(messy), mb.TRUNCATE, c["ws"],
+                                         ext_shortlist=torch.tensor(messy, dtype=torch.int32, device="cuda"), taps=True)
+    torch.cuda.synchronize()
+    ref = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, len(clean), O.TRUNCATE, ext_shortlist=clean)
+    assert np.array_equal(taps["tok_ids"].cpu().numpy(), ref["tok_ids"])
+    np.testing.assert_allclose(taps["tok_w"].cpu().numpy(), ref["tok_w"], rtol=1e-6, atol=1e-12)
+    assert taps["seg_expert"].cpu().tolist() == sorted(clean) + [-1] * (len(messy) - len(clean))
+    assert taps["seg_off"].cpu().numpy()[:len(clean) + 1].tolist() == ref["seg_off"].tolist()
+    assert int(taps["n_loaded"][0]) == len(ref["loaded"])
+    assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)
