@@ -24,9 +24,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM traffic (bytes fetched + written) of one gate/up-pass launch at the default workload (olmoe_m63, B=32,
 # substitution; mean over the six weight sets, 28.5 loaded experts), from the two rocprofv3 --pmc runs summarised
-# in profiles/gateup_olmoe_m63_B32_hbm_traffic.md: FETCH_SIZE 117921.2 x 2.0 (copy-kernel calibration) + WRITE_SIZE
-# 1008.0 KiB.  Reported only for that workload.
-MEASURED_TRAFFIC_BYTES = int((117921.2 * 2.0 + 1008.0) * 1024)
+# in profiles/gateup_olmoe_m63_B32_hbm_traffic.md: FETCH_SIZE 117925.2 x 2.0 (copy-kernel calibration) + WRITE_SIZE
+# 1011.6 KiB.  Reported only for that workload.
+MEASURED_TRAFFIC_BYTES = int((117925.2 * 2.0 + 1011.6) * 1024)
 
 
 def parse_args():
