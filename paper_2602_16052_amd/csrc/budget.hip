@@ -61,9 +61,10 @@ __device__ __forceinline__ double column_sums_staged(const double *__restrict__ 
 // Groups the surviving (token, slot) pairs by expert: segment i holds the pairs routed to
 // seg_expert[i], tokens ascending.  Run by one whole workgroup; one wave per segment at a time,
 // 64 tokens per ballot.  The routing table is staged in LDS slot-major (lanes read consecutive
-// words) when it fits.  items[0].x receives the number L of non-empty segments and items[1 + r]
-// (segment, expert, offset, size) of the one with rank r when they are ordered by size, largest
-// first (ties: lower segment first) - the order in which the expert passes hand them out.
+// words) when it fits.  items receives the work items of the expert passes: the non-empty segments
+// ordered by size, largest first (ties: lower segment first), each cut into piece_count(size) pieces of
+// (almost) equal size; items[0].x = number of pieces, items[1 + r] = (segment, expert, offset, size) of
+// piece r - the order in which the expert passes hand them out.
 // lds: (3 B + 1 + (staged ? M k : 0)) int32.
 __device__ void build_segments(const int32_t *tok_ids, int M, int k, int B, int staged, const int32_t *seg_expert,
                                int32_t *seg_off, int32_t *perm, int32_t *n_loaded, int4 *items, int32_t *lds) {
@@ -92,10 +93,11 @@ __device__ void build_segments(const int32_t *tok_ids, int M, int k, int B, int 
   }
   __syncthreads();
   if (wave == 0) {  // exclusive scan of the sizes, 64 segments per step
-    int run = 0, loaded = 0;
+    int run = 0, loaded = 0, pieces = 0;
     for (int i0 = 0; i0 < B; i0 += kWave) {
       const int i = i0 + lane;
       const int c = i < B ? sz[i] : 0;
+      pieces += piece_count(c);
       int incl = c;
 #pragma unroll
       for (int sft = 1; sft < kWave; sft <<= 1) {
@@ -109,9 +111,11 @@ __device__ void build_segments(const int32_t *tok_ids, int M, int k, int B, int 
       run += __shfl(incl, kWave - 1, kWave);
       loaded += __popcll(__ballot(c > 0));
     }
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) pieces += __shfl_xor(pieces, sft, kWave);
     if (lane == 0) {
       seg_off[B] = run;
-      items[0] = int4{loaded, 0, 0, 0};
+      items[0] = int4{pieces, 0, 0, 0};
       if (n_loaded) *n_loaded = loaded;
       cnt[B] = run;
     }
@@ -120,9 +124,10 @@ __device__ void build_segments(const int32_t *tok_ids, int M, int k, int B, int 
   for (int i = tid; i < B; i += blockDim.x) {
     const int c = sz[i];
     if (c > 0) {
-      int r = 0;
-      for (int j = 0; j < B; ++j) r += (sz[j] > c || (sz[j] == c && j < i)) ? 1 : 0;
-      items[1 + r] = int4{i, sexp[i], cnt[i], c};
+      int first = 0;  // pieces of the segments that rank before this one
+      for (int j = 0; j < B; ++j) first += (sz[j] > c || (sz[j] == c && j < i)) ? piece_count(sz[j]) : 0;
+      const int q = piece_count(c), len = (c + q - 1) / q;
+      for (int p = 0; p < q; ++p) items[1 + first + p] = int4{i, sexp[i], cnt[i] + p * len, min(len, c - p * len)};
     }
   }
   const int P = cnt[B];

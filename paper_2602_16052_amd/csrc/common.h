@@ -109,6 +109,19 @@ __device__ inline void mixing_weights(const double *g, const int32_t *sel, int k
 
 constexpr int kMaxDownSplits = 4;  // K-split copies of the per-pair outputs y
 
+// The LDS-tiled expert passes take up to 128 pairs (8 token tiles of 16) per walk over an expert's weights.
+// A longer segment is cut into ceil(c / 128) pieces of (almost) equal size, each a work item of its own, so
+// that its walks run side by side on different compute units instead of one after the other.
+constexpr int kPiecePairs = 128;
+__host__ __device__ inline int piece_count(int c) { return (c + kPiecePairs - 1) / kPiecePairs; }
+// Upper bound on the pieces of n_seg well-formed segments (disjoint, at most one pair per token each).
+inline int items_capacity(int n_seg, int64_t M, int64_t k) {
+  const int64_t a = (int64_t)n_seg * ((M + kPiecePairs - 1) / kPiecePairs), b = n_seg + M * k / kPiecePairs;
+  return (int)(a < b ? a : b);
+}
+constexpr int kSelfMaxTokens = 1024;  // largest tree for which the expert passes derive their segments themselves
+constexpr int kSelfMaxExperts = 256;  // ... and the largest shortlist
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Workspace carve-up shared by all entry points (host).
@@ -121,9 +134,9 @@ struct Workspace {
   int32_t *seg_expert;  // [N]
   int32_t *seg_off;   // [N + 1]
   int32_t *perm;      // [M * k]
-  int4 *items;        // [N + 1] count, then (segment, expert, offset, size) of the non-empty segments
-  int4 *pub_items;    // [N + 1] the same table as published by a self-segmenting gate/up pass
-  int32_t *pub_lists; // [min(N, 256), min(M, 1024)] its pair lists
+  int4 *items;        // [items_capacity(N, M, k) + 1] count, then (segment, expert, offset, size) of every piece
+  int4 *pub_items;    // [as items] the same table as published by a self-segmenting gate/up pass
+  int32_t *pub_lists; // [work items of that mode, kPiecePairs] its pair lists
   int32_t *n_loaded;  // [1]
   int32_t *done;      // [1 + N] ticket counter of the budget stage, then surviving pairs per shortlist rank
   void *act;          // [M * k, F] dtype
@@ -151,9 +164,11 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
   w.seg_expert = static_cast<int32_t *>(take(sizeof(int32_t) * N));
   w.seg_off = static_cast<int32_t *>(take(sizeof(int32_t) * (N + 1)));
   w.perm = static_cast<int32_t *>(take(sizeof(int32_t) * M * k));
-  w.items = static_cast<int4 *>(take(sizeof(int4) * (N + 1)));
-  w.pub_items = static_cast<int4 *>(take(sizeof(int4) * (N + 1)));
-  w.pub_lists = static_cast<int32_t *>(take(sizeof(int32_t) * (N < 256 ? N : 256) * (M < 1024 ? M : 1024)));
+  w.items = static_cast<int4 *>(take(sizeof(int4) * (items_capacity((int)N, M, k) + 1)));
+  w.pub_items = static_cast<int4 *>(take(sizeof(int4) * (items_capacity((int)N, M, k) + 1)));
+  w.pub_lists = static_cast<int32_t *>(
+      take(sizeof(int32_t) * kPiecePairs *
+           items_capacity((int)(N < kSelfMaxExperts ? N : kSelfMaxExperts), M < kSelfMaxTokens ? M : kSelfMaxTokens, k)));
   w.n_loaded = static_cast<int32_t *>(take(sizeof(int32_t)));
   w.done = static_cast<int32_t *>(take(sizeof(int32_t) * (1 + N)));
   w.act = take(es * M * k * F);
@@ -176,13 +191,15 @@ hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int
                          float *tok_w, int32_t *seg_expert, int32_t *seg_off, int32_t *perm, int32_t *n_loaded,
                          int4 *items, int32_t *done, bool done_is_zero, bool want_segments, double *score_scratch,
                          hipStream_t st);
-// items: table of the non-empty segments ([n_seg + 1] int4 of scratch); items_ready says that the budget
-// stage has already filled it from the same segment arrays, otherwise it is built first.
+// items: table of the work items ([items_capacity(n_seg, M, k) + 1] int4 of scratch: the non-empty segments,
+// those above kPiecePairs pairs cut into pieces); items_ready says that the budget stage has already filled
+// it from the same segment arrays, otherwise it is built first.
 // rank_count, shortlist (may be NULL): the shortlist in rank order ([n_seg]) and the surviving pairs of each
 // of its experts, from the budget stage; when given and the shape allows (expert_ffn_self_segmenting),
 // every workgroup derives its segment from them and tok_ids itself, and seg_expert / seg_off / perm /
-// items are not read.  pub_items ([n_seg + 1] int4) and pub_lists ([n_seg, M] int32) are scratch in which the gate/up pass
-// of that mode leaves its segments for the down pass (NULL: the down pass derives them again).
+// items are not read.  pub_items (like items) and pub_lists ([work items, kPiecePairs] int32) are scratch in
+// which the gate/up pass of that mode leaves its work items for the down pass (NULL: the down pass derives
+// them again).
 // trace (may be NULL): 3 events recorded after the gate/up pass, the down pass and the combine.
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,

@@ -13,8 +13,10 @@
 // streams the same number of weight bytes.  Per chunk each wave loads its rows with fully
 // coalesced 16-byte loads, parks them in a wave-private, XOR-swizzled LDS tile and reads them
 // back in MFMA operand layout; the token chunk is loaded once per workgroup into a shared LDS
-// tile (double-buffered up to 4 token tiles; one 32 KB buffer and a second barrier for 8).  (Loading operands from global memory directly in MFMA layout costs a
-// cache-line lookup per lane and saturates the texture-address path long before HBM.)
+// tile (double-buffered up to 4 token tiles; one 32 KB buffer and a second barrier for 8).  (Loading
+// operands from global memory directly in MFMA layout costs a cache-line lookup per lane and saturates
+// the texture-address path long before HBM.)  A segment of more than 128 pairs is cut into pieces that
+// are work items of their own: its walks over the expert run side by side, not one after the other.
 // Workgroups start their K walk at staggered offsets: weight rows are a power-of-two stride
 // apart, and equal offsets would pile the concurrent reads onto the same memory channels.
 // Shapes whose K is not a multiple of 128 take a simpler direct-load variant of the same tiling.
@@ -29,6 +31,7 @@
 namespace moespec {
 
 constexpr int kFfnThreads = 256;
+static_assert(kSelfMaxExperts <= kFfnThreads, "one thread per shortlist rank");
 constexpr int kFfnWaves = kFfnThreads / kWave;
 constexpr int kMaxTiles = 8;  // token tiles of 16 per pass over the weights
 
@@ -125,37 +128,47 @@ __device__ __forceinline__ bool xcd_map(int tiles, int L, int &rank, int &tile) 
   tile = w % tiles;
   return w < hi;
 }
-// items[0].x = number of non-empty segments L; items[1 + r] = (segment index, expert, offset, size)
-// of the r-th largest non-empty segment.  The table has n_seg + 1 entries.
-__device__ __forceinline__ int4 xcd_item(int tiles, int n_seg, const int4 *__restrict__ items, int &tile, int &rank) {
+// items[0].x = number of work items L; items[1 + r] = (segment index, expert, offset, size) of item r: the
+// non-empty segments, largest first, each cut into piece_count(size) pieces.  The table has cap + 1 entries.
+__device__ __forceinline__ int4 xcd_item(int tiles, int cap, const int4 *__restrict__ items, int &tile, int &rank) {
   int L = items[0].x;
-  L = L < 0 ? 0 : (L > n_seg ? n_seg : L);
+  L = L < 0 ? 0 : (L > cap ? cap : L);
   return xcd_map(tiles, L, rank, tile) ? items[1 + rank] : int4{-1, -1, 0, 0};
 }
 // The table above built from segment arrays that did not come from the budget stage.  One workgroup.
+// Only well-formed segments take part (inside the pair table, at most one pair per token), and only as
+// long as their pieces fit the table (they always do when the segments are disjoint).
 __global__ __launch_bounds__(256) void segment_items_kernel(const int32_t *__restrict__ seg_expert,
-                                                            const int32_t *__restrict__ seg_off, int n_seg,
-                                                            int4 *__restrict__ items) {
-  __shared__ int n_nonempty;
-  if (threadIdx.x == 0) n_nonempty = 0;
+                                                            const int32_t *__restrict__ seg_off, int n_seg, int M,
+                                                            int k, int cap, int4 *__restrict__ items) {
+  __shared__ int n_items;
+  if (threadIdx.x == 0) n_items = 0;
   __syncthreads();
+  auto size_of = [&](int j) {
+    const int lo = seg_off[j], c = seg_off[j + 1] - lo;
+    return (lo >= 0 && c > 0 && c <= M && (long long)lo + c <= (long long)M * k) ? c : 0;
+  };
   for (int i = threadIdx.x; i < n_seg; i += blockDim.x) {
-    const int lo = seg_off[i], c = seg_off[i + 1] - lo;
+    const int c = size_of(i);
     if (c > 0) {
-      int r = 0;
+      int first = 0;  // pieces of the segments that rank before this one
       for (int j = 0; j < n_seg; ++j) {
-        const int cj = seg_off[j + 1] - seg_off[j];
-        r += (cj > c || (cj == c && j < i)) ? 1 : 0;
+        const int cj = size_of(j);
+        first += (cj > c || (cj == c && j < i)) ? piece_count(cj) : 0;
       }
-      items[1 + r] = int4{i, seg_expert[i], lo, c};
-      atomicAdd(&n_nonempty, 1);
+      const int q = piece_count(c), len = (c + q - 1) / q, lo = seg_off[i];
+      if (first + q <= cap) {
+        for (int p = 0; p < q; ++p)
+          items[1 + first + p] = int4{i, seg_expert[i], lo + p * len, min(len, c - p * len)};
+        atomicAdd(&n_items, q);
+      }
     }
   }
   __syncthreads();
-  if (threadIdx.x == 0) items[0] = int4{n_nonempty, 0, 0, 0};
+  if (threadIdx.x == 0) items[0] = int4{n_items, 0, 0, 0};
 }
-// Workgroups of a pass: room for whole rounds of 8 segments.
-inline int xcd_grid(int tiles, int n_seg) { return kXcds * tiles * ((n_seg + kXcds - 1) / kXcds); }
+// Workgroups of a pass: room for whole rounds of 8 work items.
+inline int xcd_grid(int tiles, int n_items) { return kXcds * tiles * ((n_items + kXcds - 1) / kXcds); }
 
 // Start offset (elements) of a wave's walk over K: 128 elements (256 bytes) apart for consecutive waves.
 __device__ __forceinline__ int k_stagger(int wave_id, int K) { return (int)(((long long)wave_id * 128) % K); }
@@ -372,21 +385,21 @@ __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt
   __syncthreads();  // the LDS tiles may be reused by the caller's next pass
 }
 
-// The workgroup's segment derived on the spot (fused layer, small trees).  shortlist[r] = expert with
+// The workgroup's work item derived on the spot (fused layer, small trees).  shortlist[r] = expert with
 // rank r in the shortlist (descending aggregate score, which is also roughly descending segment size),
-// rank_count[r] = number of its surviving pairs, tok_ids = restricted routing table [M, k].  The
-// workgroup takes the shortlisted expert with pairs that xcd_map assigns to it and collects its pairs in token order
-// into plist (LDS, up to M entries).  Everything is read in one round of independent loads.
+// rank_count[r] = number of its surviving pairs, tok_ids = restricted routing table [M, k].  The work items
+// are the pieces (piece_count per expert) of the shortlisted experts in rank order; the workgroup takes the
+// one that xcd_map assigns to it and collects that piece's pairs in token order into plist (LDS,
+// kPiecePairs entries).  The tables are read in one round of independent loads per 256 tokens.
 // Requires B <= kFfnThreads, k <= kSelfMaxK, M <= kSelfMaxTokens.  misc: 8 int32 of LDS scratch.
-// Called by every thread of the workgroup (it synchronises).  Returns the expert (-1: no such rank) and the
-// number of shortlisted experts that have pairs.
-constexpr int kSelfMaxTokens = 1024;  // plist entries
+// Called by every thread of the workgroup (it synchronises).  Returns the expert (-1: no work item) and the
+// number of work items.
 constexpr int kSelfMaxK = 16;
 __device__ __forceinline__ int self_segment(const int32_t *__restrict__ rank_count,
                                             const int32_t *__restrict__ shortlist, int B,
                                             const int32_t *__restrict__ tok_ids, int M, int k, int tiles,
-                                            int32_t *misc, int32_t *plist, int &m, int &rank, int &tile,
-                                            int &n_nonempty) {
+                                            int32_t *misc, int32_t *plist, int &m, int &item, int &tile,
+                                            int &n_items) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int ids[kSelfMaxK];
   auto load_ids = [&](int t) {
@@ -396,42 +409,55 @@ __device__ __forceinline__ int self_segment(const int32_t *__restrict__ rank_cou
   load_ids(tid);
   const int c = tid < B ? rank_count[tid] : 0;
   const int ex = tid < B ? shortlist[tid] : -1;
-  const bool nz = c > 0;
-  unsigned long long mask = __ballot(nz);
-  if (lane == 0) misc[1 + wave] = __popcll(mask);
+  const int q = c > 0 ? piece_count(c) : 0;
+  int incl = q;  // inclusive scan of the piece counts over the shortlist ranks
+#pragma unroll
+  for (int sft = 1; sft < kWave; sft <<= 1) {
+    const int v = __shfl_up(incl, sft, kWave);
+    if (lane >= sft) incl += v;
+  }
+  if (lane == kWave - 1) misc[1 + wave] = incl;
   if (tid == 0) misc[0] = -1;
   __syncthreads();
   int before = 0;
-  n_nonempty = 0;
+  n_items = 0;
   for (int w = 0; w < kFfnWaves; ++w) {
     if (w < wave) before += misc[1 + w];
-    n_nonempty += misc[1 + w];
+    n_items += misc[1 + w];
   }
-  const bool has_work = xcd_map(tiles, n_nonempty, rank, tile);
-  if (has_work && nz && before + __popcll(mask & ((1ull << lane) - 1ull)) == rank) misc[0] = ex;
+  const bool has_work = xcd_map(tiles, n_items, item, tile);
+  const int first = before + incl - q;  // first work item of this thread's expert
+  if (has_work && item >= first && item < first + q) {  // one thread at most
+    const int len = (c + q - 1) / q, p = item - first;
+    misc[0] = ex;
+    misc[5] = p * len;                 // the piece: pairs [lo, lo + m) of the expert's segment
+    misc[6] = min(len, c - p * len);
+  }
   __syncthreads();
   const int e = misc[0];
   m = 0;
   if (e < 0) return -1;
+  const int lo = misc[5];
+  m = misc[6];
   int base = 0;
-  for (int t0 = 0; t0 < M; t0 += kFfnThreads) {  // uniform trip count
+  for (int t0 = 0; t0 < M && base < lo + m; t0 += kFfnThreads) {  // uniform trip count
     const int t = t0 + tid;
     if (t0 > 0) load_ids(t);
     int slot = -1;
 #pragma unroll
     for (int j = 0; j < kSelfMaxK; ++j)
       if (ids[j] == e) slot = j;
-    mask = __ballot(slot >= 0);
+    const unsigned long long mask = __ballot(slot >= 0);
     __syncthreads();  // everybody has read the wave counts of the previous round
     if (lane == 0) misc[1 + wave] = __popcll(mask);
     __syncthreads();
-    before = base;
-    for (int w = 0; w < wave; ++w) before += misc[1 + w];
-    if (slot >= 0) plist[before + __popcll(mask & ((1ull << lane) - 1ull))] = t * k + slot;
+    int pos = base;
+    for (int w = 0; w < wave; ++w) pos += misc[1 + w];
+    pos += __popcll(mask & ((1ull << lane) - 1ull)) - lo;
+    if (slot >= 0 && pos >= 0 && pos < m) plist[pos] = t * k + slot;
     for (int w = 0; w < kFfnWaves; ++w) base += misc[1 + w];
   }
   __syncthreads();
-  m = base;
   return e;
 }
 
@@ -480,29 +506,29 @@ __device__ __forceinline__ void gateup_lds(const uint16_t *wt0, const uint16_t *
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
     const uint16_t *__restrict__ h, const uint16_t *__restrict__ w_gate, const uint16_t *__restrict__ w_up,
     const int4 *__restrict__ items, const int32_t *__restrict__ perm, const int32_t *__restrict__ rank_count,
-    const int32_t *__restrict__ shortlist, const int32_t *__restrict__ tok_ids, int n_seg, int M, int N, int k, int d,
-    int F, long long perm_len, int4 *__restrict__ pub_items, int32_t *__restrict__ pub_lists,
+    const int32_t *__restrict__ shortlist, const int32_t *__restrict__ tok_ids, int n_seg, int cap, int M, int N,
+    int k, int d, int F, long long perm_len, int4 *__restrict__ pub_items, int32_t *__restrict__ pub_lists,
     uint16_t *__restrict__ act) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
-  __shared__ int32_t own_pairs[kSelfMaxTokens];
+  __shared__ int32_t own_pairs[kPiecePairs];
   __shared__ int32_t misc[8];
   const int tiles = (F / 16 + kFfnWaves - 1) / kFfnWaves;
   int tile, rank, e, m;
   const int32_t *plist;
   if (rank_count) {
-    int n_nonempty;
-    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_nonempty);
-    // The segments found here are published for the down pass (same table format as the budget stage's):
-    // workgroup 0 writes the count, the first row tile of every segment its entry and its pair list (M slots per rank).
-    if (pub_items && blockIdx.x == 0 && threadIdx.x == 0) pub_items[0] = int4{n_nonempty, 0, 0, 0};
-    if (e < 0 || e >= N || m <= 0) return;
+    int n_items;
+    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_items);
+    // The work items found here are published for the down pass (same table format as the budget stage's):
+    // workgroup 0 writes the count, the first row tile of every item its entry and its pair list.
+    if (pub_items && blockIdx.x == 0 && threadIdx.x == 0) pub_items[0] = int4{n_items, 0, 0, 0};
+    if (e < 0 || e >= N || m <= 0 || m > kPiecePairs) return;
     if (pub_items && tile == 0) {
-      for (int p = threadIdx.x; p < m; p += kFfnThreads) pub_lists[(size_t)rank * M + p] = own_pairs[p];
-      if (threadIdx.x == 0) pub_items[1 + rank] = int4{rank, e, rank * M, m};
+      for (int p = threadIdx.x; p < m; p += kFfnThreads) pub_lists[(size_t)rank * kPiecePairs + p] = own_pairs[p];
+      if (threadIdx.x == 0) pub_items[1 + rank] = int4{rank, e, rank * kPiecePairs, m};
     }
     plist = own_pairs;
   } else {
-    const int4 it = xcd_item(tiles, n_seg, items, tile, rank);
+    const int4 it = xcd_item(tiles, cap, items, tile, rank);
     e = it.y;
     m = it.w;
     if (it.x < 0 || !segment_ok(e, it.z, m, perm_len, N)) return;
@@ -560,10 +586,10 @@ __device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt
 __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
     const uint16_t *__restrict__ act, const uint16_t *__restrict__ w_down, const int4 *__restrict__ items,
     const int32_t *__restrict__ perm, const int32_t *__restrict__ rank_count, const int32_t *__restrict__ shortlist,
-    const int32_t *__restrict__ tok_ids, int n_seg, int M, int N, int k, int d, int F, int splits,
+    const int32_t *__restrict__ tok_ids, int n_seg, int cap, int M, int N, int k, int d, int F, int splits,
     long long perm_len, float *__restrict__ y) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
-  __shared__ int32_t own_pairs[kSelfMaxTokens];
+  __shared__ int32_t own_pairs[kPiecePairs];
   __shared__ int32_t misc[8];
   // a work item is (row tile, K split): split sp sums the 128-element chunks [sp n / splits, (sp + 1) n / splits)
   // of F into its own copy of y, which the combine adds up in split order
@@ -571,12 +597,12 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
   int tile, rank, e, m;
   const int32_t *plist;
   if (rank_count) {
-    int n_nonempty;
-    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_nonempty);
-    if (e < 0 || e >= N || m <= 0) return;
+    int n_items;
+    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_items);
+    if (e < 0 || e >= N || m <= 0 || m > kPiecePairs) return;
     plist = own_pairs;
   } else {
-    const int4 it = xcd_item(tiles, n_seg, items, tile, rank);
+    const int4 it = xcd_item(tiles, cap, items, tile, rank);
     e = it.y;
     m = it.w;
     if (it.x < 0 || !segment_ok(e, it.z, m, perm_len, N)) return;
@@ -727,7 +753,7 @@ static hipError_t launch_bf16(const moespec_desc &ds, const moespec_weights &wt,
 // The self-segmenting mode needs both passes on the LDS-tiled kernels and a tree small enough for
 // their LDS scratch.
 bool expert_ffn_self_segmenting(const moespec_desc &ds, int M) {
-  return ds.dtype == MOESPEC_BF16 && ds.d % 128 == 0 && ds.d_ff % 128 == 0 && ds.n_experts <= kFfnThreads &&
+  return ds.dtype == MOESPEC_BF16 && ds.d % 128 == 0 && ds.d_ff % 128 == 0 && ds.n_experts <= kSelfMaxExperts &&
          M <= kSelfMaxTokens && ds.top_k <= kSelfMaxK;
 }
 
@@ -757,8 +783,9 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
   hipError_t e;
   if (rank_count && !(shortlist && expert_ffn_self_segmenting(ds, M) && n_seg <= kFfnThreads)) rank_count = nullptr;
   if (!rank_count && !items_ready && !items) return hipErrorInvalidValue;
+  const int cap = items_capacity(n_seg, M, k);  // work items of the LDS-tiled passes
   if (ds.dtype == MOESPEC_BF16 && !rank_count && !items_ready && (d % 128 == 0 || F % 128 == 0)) {
-    segment_items_kernel<<<1, 256, 0, st>>>(seg_expert, seg_off, n_seg, items);
+    segment_items_kernel<<<1, 256, 0, st>>>(seg_expert, seg_off, n_seg, M, k, cap, items);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   auto mark = [&](int i) {
@@ -771,19 +798,20 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
     for (int pass = 1; pass <= 2; ++pass) {
       if ((pass == 1 ? d : F) % 128 == 0) {
         if (pass == 1) {
-          const int grid = xcd_grid((F / 16 + kFfnWaves - 1) / kFfnWaves, n_seg);
+          const int grid = xcd_grid((F / 16 + kFfnWaves - 1) / kFfnWaves, cap);
           ffn_gateup_lds_kernel<<<grid, kFfnThreads, 0, st>>>(
               static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(wt.w_gate),
-              static_cast<const uint16_t *>(wt.w_up), items, perm, rank_count, shortlist, tok_ids, n_seg, M,
+              static_cast<const uint16_t *>(wt.w_up), items, perm, rank_count, shortlist, tok_ids, n_seg, cap, M,
               ds.n_experts, k, d, F, (long long)M * k, publish ? pub_items : nullptr, pub_lists,
               static_cast<uint16_t *>(act));
         } else {
-          const int grid = xcd_grid(((d / 32 + kFfnWaves - 1) / kFfnWaves) * splits, n_seg);
+          const int grid = xcd_grid(((d / 32 + kFfnWaves - 1) / kFfnWaves) * splits, cap);
           // after a self-segmenting gate/up pass the down pass reads the segments that pass has published
           ffn_down_lds_kernel<<<grid, kFfnThreads, 0, st>>>(
               static_cast<const uint16_t *>(act), static_cast<const uint16_t *>(wt.w_down),
               publish ? pub_items : items, publish ? pub_lists : perm, publish ? nullptr : rank_count, shortlist,
-              tok_ids, n_seg, M, ds.n_experts, k, d, F, splits, publish ? (long long)n_seg * M : (long long)M * k, y);
+              tok_ids, n_seg, cap, M, ds.n_experts, k, d, F, splits,
+              publish ? (long long)cap * kPiecePairs : (long long)M * k, y);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         mark(pass - 1);

@@ -43,6 +43,13 @@ SMALL = {
     # the largest expert count and top-k the descriptor check admits
     "s_bf16_n1024": wl.small_config("s_bf16_n1024", "bf16", d=64, n_experts=1024, top_k=64, d_ff=32, M=9,
                                     budgets=(64, 300, 1024), bias_alpha=0.7),
+    # segments of exactly M pairs (two experts, k = 2: every token is routed to both) around the 128-pair limit of
+    # one walk over an expert: one piece, two uneven pieces, two full pieces, three pieces
+    **{f"s_bf16_piece{M}": wl.small_config(f"s_bf16_piece{M}", "bf16", d=128, n_experts=2, top_k=2, d_ff=128, M=M,
+                                           budgets=(2,), bias_alpha=0.2) for M in (128, 129, 256, 257)},
+    # the same above the limit of the trees whose expert passes derive their own work items
+    "s_bf16_piece1100": wl.small_config("s_bf16_piece1100", "bf16", d=128, n_experts=2, top_k=2, d_ff=128, M=1100,
+                                        budgets=(2,), bias_alpha=0.2),
     # sigmoid-gated routing (an independent gate per expert instead of the softmax of Eq. (1))
     "s_bf16_sigmoid": wl.small_config("s_bf16_sigmoid", "bf16", d=256, n_experts=16, top_k=4, d_ff=128, M=45,
                                       budgets=(4, 9, 16), bias_alpha=0.8, gate="sigmoid"),
@@ -110,12 +117,12 @@ def test_layer_forward_parity_small(cases, name, policy):
                 assert torch.all(out[dropped] == 0), "tokens without a surviving expert must get exact zeros"
 
 
-@pytest.mark.parametrize("name", ["s_bf16_a", "s_bf16_self", "s_f32_a"])
+@pytest.mark.parametrize("name", ["s_bf16_a", "s_bf16_self", "s_bf16_self_big", "s_bf16_piece257", "s_f32_a"])
 def test_stage_calls_compose_to_the_fused_call(cases, name):
     """route -> budget -> expert_ffn through their own entry points equals layer_forward bit for bit."""
     c = cases(name)
     cfg = c["cfg"]
-    B = cfg.budgets[1]
+    B = cfg.budgets[min(1, len(cfg.budgets) - 1)]
     for policy in (mb.TRUNCATE, mb.SUBSTITUTE):
         r = mb.moespec_route(c["desc"], c["W_d"], c["h_d"], c["ws"])
         b = mb.moespec_budget(c["desc"], r["probs"], B, policy, c["ws"])
