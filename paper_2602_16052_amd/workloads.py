@@ -74,6 +74,10 @@ CONFIGS: Dict[str, LayerConfig] = {
                              (32, 48, 64, 96, 128), 1.2, False),
     "coarse_stack": LayerConfig("coarse_stack", "bf16", 4096, 8, 2, 14336, 63,
                                 (2, 4, 6, 8), 1.5, True, n_layers=8),
+    # larger draft trees of the paper's tree-size sweep (up to 511 nodes) on the OLMoE shape: segments of more
+    # than 128 pairs, which the expert passes cut into pieces
+    "olmoe_m255": LayerConfig("olmoe_m255", "bf16", 2048, 64, 8, 1024, 255, (16, 32, 64), 1.5, True),
+    "olmoe_m511": LayerConfig("olmoe_m511", "bf16", 2048, 64, 8, 1024, 511, (16, 32, 64), 1.5, True),
 }
 CONFIG_ORDER = ("tiny_f32", "olmoe_m63", "olmoe_m127", "fine_m127", "coarse_stack")
 

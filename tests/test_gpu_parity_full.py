@@ -34,7 +34,7 @@ FULL["olmoe_m63_sigmoid"] = dataclasses.replace(wl.CONFIGS["olmoe_m63"], name="o
                                                 budgets=(16, 32, 64))
 
 
-@pytest.fixture(scope="module", params=["olmoe_m63", "olmoe_m127", "fine_m127", "olmoe_m63_sigmoid"])
+@pytest.fixture(scope="module", params=["olmoe_m63", "olmoe_m127", "fine_m127", "olmoe_m63_sigmoid", "olmoe_m511"])
 def full_case(request):
     cfg = FULL[request.param]
     t0 = time.time()
