@@ -104,7 +104,8 @@ __device__ __forceinline__ void stream_rows(const uint16_t *a0, const uint16_t *
 
 // Workgroup -> (segment, row tile) for the LDS-tiled passes.  Workgroups are handed to the 8 XCDs
 // round-robin by linear id, and each XCD has an L2 of its own and a share of the chip's streaming
-// bandwidth.  Only non-empty segments take part, largest first.  Whole rounds of 8 segments are dealt
+// bandwidth.  The work items are the non-empty segments, largest first (a segment of more than 128 pairs
+// counts as several, one per piece; "segment" below means work item).  Whole rounds of 8 segments are dealt
 // one segment per XCD (all row tiles of a segment get ids that are equal modulo 8, so that its token
 // rows are fetched into one L2); the L mod 8 segments left over (all of them when L < 8) have their
 // row tiles cut into 8 equal contiguous ranges, one per XCD, so that every XCD streams the same
@@ -112,7 +113,7 @@ __device__ __forceinline__ void stream_rows(const uint16_t *a0, const uint16_t *
 // round-robin in id order, two per unit, and a workgroup with many token tiles runs slower than one
 // with few (more LDS and matrix work per weight byte); in this order the heavy workgroups of the
 // first rounds share their compute unit with the light ones of the later rounds, or with nothing.
-// Returns false if the workgroup has no work.  L = number of non-empty segments.
+// Returns false if the workgroup has no work.  L = number of work items.
 constexpr int kXcds = 8;
 __device__ __forceinline__ bool xcd_map(int tiles, int L, int &rank, int &tile) {
   const int x = blockIdx.x % kXcds, j = blockIdx.x / kXcds;

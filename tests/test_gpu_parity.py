@@ -34,7 +34,7 @@ SMALL = {
     "s_bf16_split": wl.small_config("s_bf16_split", "bf16", d=128, n_experts=4, top_k=2, d_ff=4096, M=20,
                                     budgets=(2, 4), bias_alpha=0.5),
     # a tree beyond every small-tree limit: segments read from perm, routing table not staged in LDS
-    # (M k > 8192), several 128-pair rounds per segment
+    # (M k > 8192), many pieces of up to 128 pairs per segment
     "s_bf16_m5000": wl.small_config("s_bf16_m5000", "bf16", d=128, n_experts=6, top_k=2, d_ff=128, M=5000,
                                     budgets=(2, 4, 6), bias_alpha=0.4),
     # a very large tree: the aggregate scores are summed once instead of in every workgroup
