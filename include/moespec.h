@@ -257,6 +257,21 @@ moespec_status moespec_oracle_ranking(const moespec_desc *desc, const moespec_we
                                       int32_t M, int32_t B, int32_t *ranking, double *err,
                                       void *ws, size_t ws_bytes, void *hip_stream);
 
+/*
+ * Measurement aid - the practical ceiling of the roofline that bounds the expert passes: a plain streaming
+ * read of `bytes` bytes (16-byte loads, eight in flight per lane, every byte read once), timed by the caller.
+ * The expert passes are bound by HBM bandwidth (Section 2.2 of the paper: loading the unique experts
+ * dominates verification); this kernel shows how much of the published peak a read-only stream reaches on
+ * the machine at hand.
+ *   buf      [bytes] in (device), 16-byte aligned; bytes a multiple of 16, 16 <= bytes < 2^40
+ *   checksum [MOESPEC_STREAM_READ_WORDS] uint32 in/out (device): workgroup b ADDS the sum modulo 2^32 of the
+ *            32-bit words it has read to word b (one writer per word, no atomics); the sum of all words
+ *            modulo 2^32 is the checksum of the buffer; the caller zeroes the array
+ * Errors: MOESPEC_ERR_INVALID_ARG for a NULL or misaligned pointer or a size outside the range.
+ */
+#define MOESPEC_STREAM_READ_WORDS 256
+moespec_status moespec_stream_read(const void *buf, size_t bytes, uint32_t *checksum, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ GATE_SOFTMAX, GATE_SIGMOID = 0, 1
 EXPORTS = ("moespec_abi_version", "moespec_status_string", "moespec_check_desc", "moespec_workspace_bytes",
            "moespec_route", "moespec_budget", "moespec_expert_ffn", "moespec_layer_forward",
            "moespec_calibration_count", "moespec_static_shortlist", "moespec_coverage_curve",
-           "moespec_reconstruction_error", "moespec_oracle_ranking")
+           "moespec_reconstruction_error", "moespec_oracle_ranking", "moespec_stream_read")
 
 
 class MoeSpecError(RuntimeError):
@@ -102,6 +102,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moespec_oracle_ranking.restype = c_int32
     lib.moespec_oracle_ranking.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_void_p,
                                            c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.moespec_stream_read.restype = c_int32
+    lib.moespec_stream_read.argtypes = [c_void_p, c_size_t, c_void_p, c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -402,3 +404,21 @@ def moespec_oracle_ranking(desc: LayerDesc, weights: Dict[str, torch.Tensor], h:
                                                _ptr(ranking), _ptr(err), _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "moespec_oracle_ranking")
     return ranking, err
+
+
+STREAM_READ_WORDS = 256
+
+
+def moespec_stream_read(buf: torch.Tensor, checksum: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Measurement aid: stream `buf` (contiguous, a multiple of 16 bytes) once through a plain read kernel.
+    Every workgroup adds the sum modulo 2^32 of the 32-bit words it read to its word of `checksum`
+    (int32 [STREAM_READ_WORDS], zeroed here if not given); `checksum.sum()` modulo 2^32 is the buffer's checksum."""
+    if not (buf.is_cuda and buf.is_contiguous()):
+        raise ValueError("buf: expected a contiguous GPU tensor")
+    if checksum is None:
+        checksum = torch.zeros(STREAM_READ_WORDS, dtype=torch.int32, device=buf.device)
+    st = load_library().moespec_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(),
+                                            _ptr(checksum, torch.int32, STREAM_READ_WORDS, "checksum"),
+                                            _stream(stream))
+    _check(st, "moespec_stream_read")
+    return checksum

@@ -233,4 +233,11 @@ moespec_status moespec_oracle_ranking(const moespec_desc *desc, const moespec_we
                                         st));
 }
 
+moespec_status moespec_stream_read(const void *buf, size_t bytes, uint32_t *checksum, void *hip_stream) {
+  if (!buf || !checksum || !aligned16(buf) || (reinterpret_cast<uintptr_t>(checksum) & 3u) != 0)
+    return MOESPEC_ERR_INVALID_ARG;
+  if (bytes < 16 || bytes % 16 != 0 || bytes >= ((size_t)1 << 40)) return MOESPEC_ERR_INVALID_ARG;
+  return from_hip(launch_stream_read(buf, bytes, checksum, static_cast<hipStream_t>(hip_stream)));
+}
+
 }  // extern "C"

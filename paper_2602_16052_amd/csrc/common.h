@@ -220,6 +220,7 @@ hipError_t launch_coverage_curve(const double *scores, int N, double *curve, hip
 hipError_t launch_oracle_ranking(const moespec_desc &ds, const float *y, int splits, size_t split_stride,
                                  const int32_t *tok_ids, const float *tok_w, int M, int B, double *pair_gram,
                                  double *gram, int32_t *ranking, double *err, hipStream_t st);
+hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *checksum, hipStream_t st);
 hipError_t launch_reconstruction_error(const moespec_desc &ds, const void *out_budgeted, const void *out_full, int M,
                                        double *part, double *err, hipStream_t st);
 

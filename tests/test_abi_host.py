@@ -157,6 +157,18 @@ def test_oracle_ranking_rejects_bad_arguments(lib):
     assert f(ctypes.byref(cd), None, P, 8, 4, P, P, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
 
 
+def test_stream_read_rejects_bad_arguments(lib):
+    f = lib.moespec_stream_read
+    P, C = 0x50000, 0x60000
+    assert f(None, 1024, C, None) == mb.ERR_INVALID_ARG
+    assert f(P, 1024, None, None) == mb.ERR_INVALID_ARG
+    assert f(P + 8, 1024, C, None) == mb.ERR_INVALID_ARG       # buffer not 16-byte aligned
+    assert f(P, 1024, C + 2, None) == mb.ERR_INVALID_ARG       # checksum word not 4-byte aligned
+    assert f(P, 0, C, None) == mb.ERR_INVALID_ARG
+    assert f(P, 1000, C, None) == mb.ERR_INVALID_ARG           # not a multiple of 16
+    assert f(P, 1 << 40, C, None) == mb.ERR_INVALID_ARG
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     d = D()

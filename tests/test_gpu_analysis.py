@@ -146,3 +146,15 @@ def test_oracle_ranking_matches_the_cpu_greedy(case):
     e = mb.moespec_reconstruction_error(desc, out, full, c["ws"])
     torch.cuda.synchronize()
     assert float(e[0]) == pytest.approx(float(err[B - 1]), abs=3 * tol, rel=0.2)
+
+
+@pytest.mark.parametrize("nbytes", [16, 4096, 1 << 20, (1 << 20) + 48, 24 << 20])
+def test_stream_read_checksum(nbytes):
+    """The streaming-read measurement kernel touches every byte once: its checksum is the sum of all 32-bit words."""
+    g = torch.Generator(device="cuda").manual_seed(nbytes)
+    buf = torch.randint(-2**31, 2**31 - 1, (nbytes // 4,), dtype=torch.int32, device="cuda", generator=g)
+    got = mb.moespec_stream_read(buf)
+    got = mb.moespec_stream_read(buf, got)          # a second call adds to the same words
+    torch.cuda.synchronize()
+    want = (2 * int(buf.cpu().numpy().astype(np.int64).sum())) % (1 << 32)
+    assert int(got.cpu().numpy().astype(np.int64).sum()) % (1 << 32) == want
