@@ -28,13 +28,18 @@ def routing_reference(cfg, h_o, W_o, B, policy):
     return r
 
 
-# a second routing scheme at full size: the OLMoE-shaped layer with a sigmoid gate per expert
+# a second routing scheme at full size: the OLMoE-shaped layer with a sigmoid gate per expert; and the benchmark
+# workload drawn from other seeds (different expert popularity order, hidden rows and weights)
 FULL = dict(wl.CONFIGS)
+for _seed in (1, 2, 3, 4):
+    FULL[f"olmoe_m63_seed{_seed}"] = dataclasses.replace(wl.CONFIGS["olmoe_m63"], name=f"olmoe_m63_seed{_seed}",
+                                                         seed=_seed, budgets=(32, 64))
 FULL["olmoe_m63_sigmoid"] = dataclasses.replace(wl.CONFIGS["olmoe_m63"], name="olmoe_m63_sigmoid", gate="sigmoid",
                                                 budgets=(16, 32, 64))
 
 
-@pytest.fixture(scope="module", params=["olmoe_m63", "olmoe_m127", "fine_m127", "olmoe_m63_sigmoid", "olmoe_m511"])
+@pytest.fixture(scope="module", params=["olmoe_m63", "olmoe_m127", "fine_m127", "olmoe_m63_sigmoid", "olmoe_m511",
+                                        "olmoe_m63_seed1", "olmoe_m63_seed2", "olmoe_m63_seed3", "olmoe_m63_seed4"])
 def full_case(request):
     cfg = FULL[request.param]
     t0 = time.time()
