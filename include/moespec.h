@@ -2,8 +2,8 @@
  * moespec.h - C ABI of the budgeted MoE-layer forward that verifies an M-token draft tree
  * (MoE-Spec expert budgeting), implemented as HIP kernels for gfx950 (MI355X).
  *
- * The calls follow the paper's problem statement (Algorithm 1: "hidden states h_1..h_M, budget B,
- * policy -> MoE output for each token") split at its three stages:
+ * The calls take the inputs and produce the output of Algorithm 1 (the M hidden rows of the draft tree, the
+ * budget and the coverage policy in; one MoE output row per token out), split at its three stages:
  *
  *   moespec_route          Eq. (1) router softmax, Section 2.1 per-token top-k and mixing weights
  *   moespec_budget         Eq. (5) per-expert aggregation, top-B shortlist (Section 3.2), Eq. (7)/(8)
@@ -77,7 +77,7 @@ typedef struct {
   int32_t d_ff;      /* expert intermediate size F                                          */
   int32_t dtype;     /* moespec_dtype: storage of h, the weights, residual and out          */
   int32_t renorm;    /* 0: mixing weights are the raw g_i; 1: g_i / sum over the selected   */
-                     /* set (Section 2.1: "depending on the architecture")                  */
+                     /* set (which one applies is a property of the model, Section 2.1)     */
   int32_t gate;      /* moespec_gate                                                        */
 } moespec_desc;
 

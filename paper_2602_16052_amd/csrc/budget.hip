@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
     mixing_weights(g, sel, k, renorm, wsel, wsel + ((k + 1) & ~1));
     __syncthreads();
     for (int j = tid; j < k; j += blockDim.x) {
-      const bool keep = inS[sel[j]] != 0;
+      const bool keep = (uint32_t)sel[j] < (uint32_t)N && inS[sel[j]] != 0;  // an unfilled slot (NaN scores) is dropped
       tok_ids[(size_t)t * k + j] = keep ? sel[j] : -1;
       tok_w[(size_t)t * k + j] = keep ? (float)wsel[j] : 0.0f;
       if (keep) atomicAdd(&done[1 + pos[sel[j]]], 1);
@@ -248,16 +248,15 @@ __global__ __launch_bounds__(kBudgetThreads) void budget_kernel(
   } else {
     // Top-k inside S by g_i(h_t); weights over the constrained selection.  Slots stay unfilled (-1)
     // only when an external shortlist names fewer than k valid experts.
-    for (int j = tid; j < k; j += blockDim.x) sel[j] = -1;
-    __syncthreads();
     select_topk(g, inS, N, k, sel, rank);
     __syncthreads();
     mixing_weights(g, sel, k, renorm, wsel, wsel + ((k + 1) & ~1));
     __syncthreads();
     for (int j = tid; j < k; j += blockDim.x) {
-      tok_ids[(size_t)t * k + j] = sel[j];
-      tok_w[(size_t)t * k + j] = (float)wsel[j];
-      if (sel[j] >= 0) atomicAdd(&done[1 + pos[sel[j]]], 1);
+      const bool filled = (uint32_t)sel[j] < (uint32_t)N;
+      tok_ids[(size_t)t * k + j] = filled ? sel[j] : -1;
+      tok_w[(size_t)t * k + j] = filled ? (float)wsel[j] : 0.0f;
+      if (filled) atomicAdd(&done[1 + pos[sel[j]]], 1);
     }
   }
 

@@ -63,11 +63,14 @@ __device__ __forceinline__ double wave_max(double v) {
 // synchronises again before reading sel.  The n x n comparisons are spread over the whole workgroup:
 // thread (i, part) counts the rivals of candidate i inside its part of the index range and adds its
 // count to rank[i] with an integer LDS atomic (order-independent, hence deterministic).
+// Every slot of sel is first set to -1: when a value is NaN no comparison holds, several candidates then
+// count rank 0 and some slots are never claimed; those stay -1 (an unfilled slot) instead of stale LDS.
 __device__ inline void select_topk(const double *v, const uint8_t *member, int n, int k, int32_t *sel, int32_t *rank) {
   const int nt = blockDim.x, tid = threadIdx.x;
   int np2 = 1;
   while (np2 < n) np2 <<= 1;
   for (int x = tid; x < n; x += nt) rank[x] = 0;
+  for (int x = tid; x < k; x += nt) sel[x] = -1;
   __syncthreads();
   const int parts = np2 <= nt ? nt / np2 : 1;
   const int chunk = (n + parts - 1) / parts;

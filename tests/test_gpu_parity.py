@@ -247,3 +247,33 @@ def test_external_shortlist_with_repeated_and_invalid_ids(cases):
     assert taps["seg_off"].cpu().numpy()[:len(clean) + 1].tolist() == ref["seg_off"].tolist()
     assert int(taps["n_loaded"][0]) == len(ref["loaded"])
     assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)
+
+
+@pytest.mark.parametrize("name", ["s_bf16_a", "s_bf16_self", "s_f32_a"])
+def test_non_finite_hidden_rows_leave_every_index_in_range(cases, name):
+    """A NaN hidden row makes every routing score NaN, so no ranking comparison holds and selections cannot fill
+    their slots.  The paper defines nothing for such input; the path must still finish normally, mark the
+    unfilled slots as dropped (-1, weight 0) and hand the expert passes only ids inside [0, N)."""
+    c = cases(name)
+    cfg = c["cfg"]
+    h_bad = c["h_d"].clone()
+    h_bad[min(3, cfg.M - 1), 5] = float("nan")
+    for policy in (mb.TRUNCATE, mb.SUBSTITUTE):
+        for B in cfg.budgets:
+            if policy == mb.SUBSTITUTE and B < cfg.top_k:
+                continue
+            for taps_on in (True, False):
+                res = mb.moespec_layer_forward(c["desc"], c["W_d"], h_bad, B, policy, c["ws"], taps=taps_on)
+                torch.cuda.synchronize()
+                if taps_on:
+                    taps = res[1]
+                    ids, S, perm = taps["tok_ids"].cpu().numpy(), taps["budget_ids"].cpu().numpy(), taps["perm"].cpu().numpy()
+                    assert np.all((ids >= -1) & (ids < cfg.n_experts)) and np.all((S >= -1) & (S < cfg.n_experts))
+                    assert np.all((perm >= -1) & (perm < cfg.M * cfg.top_k))
+                    assert np.all(taps["tok_w"].cpu().numpy()[ids < 0] == 0)
+    # the same workspace serves a clean call afterwards
+    out, taps = mb.moespec_layer_forward(c["desc"], c["W_d"], c["h_d"], cfg.budgets[-1], mb.TRUNCATE, c["ws"], taps=True)
+    torch.cuda.synchronize()
+    ref = O.layer_forward(c["h_o"], c["W_o"], cfg.top_k, cfg.renorm, cfg.budgets[-1], O.TRUNCATE, gate=cfg.gate)
+    assert_routing_equal(taps, ref, cfg.budgets[-1])
+    assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)

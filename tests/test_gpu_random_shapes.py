@@ -59,7 +59,7 @@ def test_random_shape_parity(i):
             torch.cuda.synchronize()
             ref = O.layer_forward(h_o, W_o, cfg.top_k, cfg.renorm, B, policy, gate=cfg.gate)
             assert_routing_equal(taps, ref, B)
-            assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype, scale_aware=True)
+            assert_out_close(out_to_numpy(out), ref["out"], cfg.dtype)
             out_plain = mb.moespec_layer_forward(desc, W_d, h_d, B, policy, ws)
             torch.cuda.synchronize()
             assert torch.equal(out_plain, out)
