@@ -205,6 +205,29 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
                                      void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * moespec_layer_forward for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results
+ * (bit for bit) as moespec_layer_forward without taps, but the scratch memory is a fixed device array inside
+ * the library, MOESPEC_STATIC_SCRATCH_BYTES large, instead of a caller-owned workspace.  The call allocates and
+ * frees nothing.
+ *   Limit     moespec_workspace_bytes(desc, M) must not exceed MOESPEC_STATIC_SCRATCH_BYTES, otherwise
+ *             MOESPEC_ERR_WORKSPACE_TOO_SMALL is returned before any launch (the OLMoE-like, 128-expert and
+ *             Mixtral-like layer shapes fit up to 127 tree tokens).
+ *   Set-up    The first call on a device looks up the array's device address (hipGetSymbolAddress, once per
+ *             device, with that device current); make that first call outside any graph capture.
+ *             MOESPEC_ERR_HIP if the look-up fails.
+ *   Sharing   Every call on one GPU uses that GPU's one array, which keeps whatever the last call left in it
+ *             (the kernels clear what they need cleared).  Calls that overlap in time on one GPU - different
+ *             streams, different host threads - race on it: order them on one stream.
+ * The array occupies MOESPEC_STATIC_SCRATCH_BYTES of every GPU the library is used on until the process ends.
+ */
+#define MOESPEC_STATIC_SCRATCH_BYTES (48u << 20)
+moespec_status moespec_layer_forward_static(const moespec_desc *desc, const moespec_weights *weights,
+                                            const void *h, int32_t M, int32_t B, int32_t policy,
+                                            const int32_t *ext_shortlist,
+                                            const void *residual, void *out, void *hip_stream);
+
+/*
  * Static ranking - Eq. (4): c_i = number of calibration tokens h with i in T_k(h).
  *   topk_ids [M, k] int32  in     natural top-k ids of a batch of calibration tokens (moespec_route);
  *                                 entries outside [0, N) are ignored

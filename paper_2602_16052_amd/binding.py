@@ -25,6 +25,7 @@ GATE_SOFTMAX, GATE_SIGMOID = 0, 1
 
 EXPORTS = ("moespec_abi_version", "moespec_status_string", "moespec_check_desc", "moespec_workspace_bytes",
            "moespec_route", "moespec_budget", "moespec_expert_ffn", "moespec_layer_forward",
+           "moespec_layer_forward_static",
            "moespec_calibration_count", "moespec_static_shortlist", "moespec_coverage_curve",
            "moespec_reconstruction_error", "moespec_oracle_ranking", "moespec_stream_read")
 
@@ -90,6 +91,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moespec_layer_forward.restype = c_int32
     lib.moespec_layer_forward.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_int32,
                                           c_void_p, c_void_p, c_void_p, POINTER(Taps), c_void_p, c_size_t, c_void_p]
+    lib.moespec_layer_forward_static.restype = c_int32
+    lib.moespec_layer_forward_static.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_int32,
+                                                 c_void_p, c_void_p, c_void_p, c_void_p]
     lib.moespec_calibration_count.restype = c_int32
     lib.moespec_calibration_count.argtypes = [POINTER(Desc), c_void_p, c_int32, c_void_p, c_void_p]
     lib.moespec_static_shortlist.restype = c_int32
@@ -347,6 +351,24 @@ def moespec_layer_forward(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: 
         _stream(stream))
     _check(st, "moespec_layer_forward")
     return (out, tap_t) if taps else out
+
+
+STATIC_SCRATCH_BYTES = 48 << 20
+
+
+def moespec_layer_forward_static(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: torch.Tensor, B: int,
+                                 policy: int, out: torch.Tensor, ext_shortlist: Optional[torch.Tensor] = None,
+                                 residual: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Algorithm 1 in one call on the library's own fixed scratch array: no workspace argument, nothing allocated
+    (``out`` is the caller's).  Returns ``out``."""
+    M, dt = h.shape[0], desc.torch_dtype
+    cd, cw = desc.c(), _weights(desc, weights, True, True)
+    st = load_library().moespec_layer_forward_static(
+        ctypes.byref(cd), ctypes.byref(cw), _ptr(h, dt, M * desc.d, "h"), M, int(B), int(policy),
+        _ptr(ext_shortlist, torch.int32, max(int(B), 0), "ext_shortlist"), _ptr(residual, dt, M * desc.d, "residual"),
+        _ptr(out, dt, M * desc.d, "out"), _stream(stream))
+    _check(st, "moespec_layer_forward_static")
+    return out
 
 
 def moespec_calibration_count(desc: LayerDesc, topk_ids: torch.Tensor, counts: torch.Tensor, stream=None) -> torch.Tensor:

@@ -1,5 +1,7 @@
 // C ABI of the library: argument validation (host only, before any launch), workspace carve-up,
 // and the sequencing of the kernel launchers.
+#include <atomic>
+
 #include "common.h"
 
 using namespace moespec;
@@ -59,11 +61,81 @@ moespec_status check_budget(const moespec_desc *ds, int32_t B, int32_t policy) {
 
 moespec_status from_hip(hipError_t e) { return e == hipSuccess ? MOESPEC_OK : MOESPEC_ERR_HIP; }
 
+
+// Scratch memory of moespec_layer_forward_static: the workspace of the other entry points as a file-scope
+// device array, so that the call allocates nothing.  Every GPU the library runs on holds its own copy at its own
+// address until the process ends.  In host code the array's name is only a handle: the device address is resolved
+// once per device with hipGetSymbolAddress and kept here; kernels are only ever given that address.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[MOESPEC_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_ptr[kMaxDevices];
+
+void *static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void *p = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  scratch_ptr[dev].store(p, std::memory_order_release);  // every thread resolves the same address: no lock needed
+  return p;
+}
+
+// The argument checks of the fused call other than those on the tree size and the workspace (desc is valid).
+moespec_status check_layer_args(const moespec_desc *desc, const moespec_weights *weights, const void *h, int32_t B,
+                                int32_t policy, const void *residual, const void *out) {
+  moespec_status s = check_weights(weights, true, true);
+  if (s != MOESPEC_OK) return s;
+  if ((s = check_budget(desc, B, policy)) != MOESPEC_OK) return s;
+  if (!h || !out || !aligned16(h) || !aligned16(out) || (residual && !aligned16(residual)))
+    return MOESPEC_ERR_INVALID_ARG;
+  return MOESPEC_OK;
+}
+
+moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *weights, const void *h,
+                                     int32_t M, int32_t B, int32_t policy, const int32_t *ext_shortlist,
+                                     const void *residual, void *out, const moespec_taps *taps, void *ws,
+                                     size_t ws_bytes, void *hip_stream) {
+  moespec_status s = check_common(desc, M, ws, ws_bytes);
+  if (s != MOESPEC_OK) return s;
+  if ((s = check_layer_args(desc, weights, h, B, policy, residual, out)) != MOESPEC_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  Workspace w = carve_workspace(*desc, M, ws);
+  // A tap replaces the workspace slot of the same intermediate, so it is written in place.
+  moespec_taps t = taps ? *taps : moespec_taps{};
+  double *probs = t.probs ? t.probs : w.probs;
+  int32_t *tok_ids = t.tok_ids ? t.tok_ids : w.tok_ids;
+  float *tok_w = t.tok_w ? t.tok_w : w.tok_w;
+  int32_t *seg_expert = t.seg_expert ? t.seg_expert : w.seg_expert;
+  int32_t *seg_off = t.seg_off ? t.seg_off : w.seg_off;
+  int32_t *perm = t.perm ? t.perm : w.perm;
+  int32_t *budget_ids = t.budget_ids ? t.budget_ids : w.budget_ids;
+  void *const *tr = t.trace_events;
+  auto mark = [&](int i) {
+    if (tr && tr[i]) (void)hipEventRecord(static_cast<hipEvent_t>(tr[i]), st);
+  };
+  // Small trees: the expert passes derive their segments themselves, and the budget stage groups the
+  // pairs only if the caller asked for the segment arrays.
+  const bool self_seg = expert_ffn_self_segmenting(*desc, M);
+  const bool want_segments = !self_seg || t.seg_off || t.perm || t.n_loaded;
+  mark(0);
+  hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, w.done, 1 + desc->n_experts, st);
+  if (e != hipSuccess) return MOESPEC_ERR_HIP;
+  mark(1);
+  e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, budget_ids, tok_ids, tok_w, seg_expert,
+                    seg_off, perm, t.n_loaded, w.items, w.done, true, want_segments, w.scores, st);
+  if (e != hipSuccess) return MOESPEC_ERR_HIP;
+  mark(2);
+  e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
+                        w.y, w.items, want_segments, self_seg ? w.done + 1 : nullptr, budget_ids, w.pub_items,
+                        w.pub_lists, st, tr ? tr + 3 : nullptr);
+  return from_hip(e);
+}
+
 }  // namespace
 
 extern "C" {
 
-int32_t moespec_abi_version(void) { return 2; }
+int32_t moespec_abi_version(void) { return 3; }
 
 const char *moespec_status_string(int32_t status) {
   switch (status) {
@@ -129,43 +201,25 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
                                      int32_t M, int32_t B, int32_t policy, const int32_t *ext_shortlist,
                                      const void *residual, void *out, const moespec_taps *taps, void *ws,
                                      size_t ws_bytes, void *hip_stream) {
-  moespec_status s = check_common(desc, M, ws, ws_bytes);
+  return layer_forward(desc, weights, h, M, B, policy, ext_shortlist, residual, out, taps, ws, ws_bytes, hip_stream);
+}
+
+moespec_status moespec_layer_forward_static(const moespec_desc *desc, const moespec_weights *weights, const void *h,
+                                            int32_t M, int32_t B, int32_t policy, const int32_t *ext_shortlist,
+                                            const void *residual, void *out, void *hip_stream) {
+  // shapes first: a descriptor error is reported as such, a layer that does not fit the array as a workspace error
+  moespec_status s = check_desc(desc);
   if (s != MOESPEC_OK) return s;
-  if ((s = check_weights(weights, true, true)) != MOESPEC_OK) return s;
-  if ((s = check_budget(desc, B, policy)) != MOESPEC_OK) return s;
-  if (!h || !out || !aligned16(h) || !aligned16(out) || (residual && !aligned16(residual)))
-    return MOESPEC_ERR_INVALID_ARG;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  Workspace w = carve_workspace(*desc, M, ws);
-  // A tap replaces the workspace slot of the same intermediate, so it is written in place.
-  moespec_taps t = taps ? *taps : moespec_taps{};
-  double *probs = t.probs ? t.probs : w.probs;
-  int32_t *tok_ids = t.tok_ids ? t.tok_ids : w.tok_ids;
-  float *tok_w = t.tok_w ? t.tok_w : w.tok_w;
-  int32_t *seg_expert = t.seg_expert ? t.seg_expert : w.seg_expert;
-  int32_t *seg_off = t.seg_off ? t.seg_off : w.seg_off;
-  int32_t *perm = t.perm ? t.perm : w.perm;
-  int32_t *budget_ids = t.budget_ids ? t.budget_ids : w.budget_ids;
-  void *const *tr = t.trace_events;
-  auto mark = [&](int i) {
-    if (tr && tr[i]) (void)hipEventRecord(static_cast<hipEvent_t>(tr[i]), st);
-  };
-  // Small trees: the expert passes derive their segments themselves, and the budget stage groups the
-  // pairs only if the caller asked for the segment arrays.
-  const bool self_seg = expert_ffn_self_segmenting(*desc, M);
-  const bool want_segments = !self_seg || t.seg_off || t.perm || t.n_loaded;
-  mark(0);
-  hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, w.done, 1 + desc->n_experts, st);
-  if (e != hipSuccess) return MOESPEC_ERR_HIP;
-  mark(1);
-  e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, budget_ids, tok_ids, tok_w, seg_expert,
-                    seg_off, perm, t.n_loaded, w.items, w.done, true, want_segments, w.scores, st);
-  if (e != hipSuccess) return MOESPEC_ERR_HIP;
-  mark(2);
-  e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
-                        w.y, w.items, want_segments, self_seg ? w.done + 1 : nullptr, budget_ids, w.pub_items,
-                        w.pub_lists, st, tr ? tr + 3 : nullptr);
-  return from_hip(e);
+  if (M < 1 || M > kMaxTokens) return MOESPEC_ERR_INVALID_ARG;
+  if ((int64_t)M * desc->top_k * (desc->d > desc->d_ff ? desc->d : desc->d_ff) >= ((int64_t)1 << 31))
+    return MOESPEC_ERR_UNSUPPORTED_SHAPE;
+  if (carve_workspace(*desc, M, nullptr).bytes > (size_t)MOESPEC_STATIC_SCRATCH_BYTES)
+    return MOESPEC_ERR_WORKSPACE_TOO_SMALL;
+  if ((s = check_layer_args(desc, weights, h, B, policy, residual, out)) != MOESPEC_OK) return s;
+  void *ws = static_scratch();  // the first GPU-touching step: every argument error has been reported by now
+  if (!ws) return MOESPEC_ERR_HIP;
+  return layer_forward(desc, weights, h, M, B, policy, ext_shortlist, residual, out, nullptr, ws, (size_t)MOESPEC_STATIC_SCRATCH_BYTES,
+                       hip_stream);
 }
 
 moespec_status moespec_calibration_count(const moespec_desc *desc, const int32_t *topk_ids, int32_t M,

@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert mb.abi_version() == 2
+    assert mb.abi_version() == 3
     assert mb.status_string(mb.OK) == "ok"
     assert "workspace" in mb.status_string(mb.ERR_WORKSPACE_TOO_SMALL)
     assert mb.status_string(99) == "unknown status"
@@ -96,6 +96,29 @@ def test_layer_forward_rejects_bad_arguments_before_any_launch(lib):
     assert _call_layer(lib, d, ws_bytes=mb.workspace_bytes(d, 8) - 1) == mb.ERR_WORKSPACE_TOO_SMALL
     assert _call_layer(lib, D(d=250)) == mb.ERR_UNSUPPORTED_SHAPE
     assert _call_layer(lib, D(dtype=3)) == mb.ERR_INVALID_ARG
+
+
+def test_static_scratch_call_rejects_bad_arguments_and_oversized_layers_before_any_launch(lib):
+    """moespec_layer_forward_static validates on the host before it touches the GPU: argument errors as in the
+    workspace call, and a layer whose scratch need exceeds the fixed array is a workspace error."""
+    def call(desc, M=8, B=8, policy=mb.SUBSTITUTE, h=0x20000, out=0x30000, wptr=0x40000, residual=None):
+        cd = desc.c()
+        w = mb.Weights(wptr, None, wptr, wptr, wptr)
+        return lib.moespec_layer_forward_static(ctypes.byref(cd), ctypes.byref(w), h, M, B, policy, None, residual,
+                                                out, None)
+    d = D()
+    assert call(d, M=0) == mb.ERR_INVALID_ARG
+    assert call(d, B=17) == mb.ERR_INVALID_ARG
+    assert call(d, B=3) == mb.ERR_INVALID_ARG                                        # B < k under substitution
+    assert call(d, h=None) == mb.ERR_INVALID_ARG
+    assert call(d, out=0x30004) == mb.ERR_INVALID_ARG
+    assert call(d, wptr=None) == mb.ERR_INVALID_ARG
+    assert call(D(d=250)) == mb.ERR_UNSUPPORTED_SHAPE
+    olmoe = mb.LayerDesc(2048, 64, 8, 1024, mb.BF16, True)
+    assert mb.workspace_bytes(olmoe, 127) <= mb.STATIC_SCRATCH_BYTES < mb.workspace_bytes(olmoe, 511)
+    assert call(olmoe, M=511, B=32) == mb.ERR_WORKSPACE_TOO_SMALL
+    header = open(os.path.join(ROOT, "include", "moespec.h")).read()
+    assert re.search(r"#define MOESPEC_STATIC_SCRATCH_BYTES \(48u << 20\)", header) and mb.STATIC_SCRATCH_BYTES == 48 << 20
 
 
 def test_stage_calls_reject_bad_arguments(lib):
