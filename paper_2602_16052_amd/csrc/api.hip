@@ -113,11 +113,25 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
   auto mark = [&](int i) {
     if (tr && tr[i]) (void)hipEventRecord(static_cast<hipEvent_t>(tr[i]), st);
   };
-  // Small trees: the expert passes derive their segments themselves, and the budget stage groups the
-  // pairs only if the caller asked for the segment arrays.
+  mark(0);
+  if (fused_prologue_ok(*desc, M) && expert_ffn_self_segmenting(*desc, M)) {
+    // Small trees: two launches leave the shortlist, the restricted routing and every loaded expert's pair
+    // list; the expert passes pick their work items from those lists.
+    hipError_t e = launch_fused_prologue(*desc, *weights, h, M, B, policy, ext_shortlist, w.partial, t.probs, t.scores,
+                                         budget_ids, t.seg_expert, tok_ids, tok_w, w.list_count, w.lists, M,
+                                         t.seg_off, t.perm, t.n_loaded, st);
+    if (e != hipSuccess) return MOESPEC_ERR_HIP;
+    mark(1);
+    mark(2);
+    e = launch_expert_ffn(*desc, *weights, h, M, B, nullptr, nullptr, nullptr, tok_ids, tok_w, residual, out, w.act,
+                          w.y, w.items, false, w.list_count, budget_ids, nullptr, nullptr, st, tr ? tr + 3 : nullptr,
+                          w.lists, M);
+    return from_hip(e);
+  }
+  // Other shapes: the expert passes derive their segments themselves where they can, and the budget stage groups
+  // the pairs only if the caller asked for the segment arrays or the passes need them.
   const bool self_seg = expert_ffn_self_segmenting(*desc, M);
   const bool want_segments = !self_seg || t.seg_off || t.perm || t.n_loaded;
-  mark(0);
   hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, w.done, 1 + desc->n_experts, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   mark(1);

@@ -122,6 +122,7 @@ inline int items_capacity(int n_seg, int64_t M, int64_t k) {
   const int64_t a = (int64_t)n_seg * ((M + kPiecePairs - 1) / kPiecePairs), b = n_seg + M * k / kPiecePairs;
   return (int)(a < b ? a : b);
 }
+constexpr int kMaxLogitSlices = 8;    // slices of the hidden dimension in the fused prologue's router projection
 constexpr int kSelfMaxTokens = 1024;  // largest tree for which the expert passes derive their segments themselves
 constexpr int kSelfMaxExperts = 256;  // ... and the largest shortlist
 
@@ -145,6 +146,9 @@ struct Workspace {
   void *act;          // [M * k, F] dtype
   float *y;           // [kMaxDownSplits][M * k, d]
   double *gram;       // [N, N + 3] scratch of the oracle ranking
+  double *partial;    // [kMaxLogitSlices, M, N] partial router projections of the fused prologue
+  int32_t *list_count;  // [N] pairs per shortlist rank (fused prologue)
+  int32_t *lists;     // [N, M] their pair lists (only for shapes the fused prologue covers)
   size_t bytes;
 };
 
@@ -177,6 +181,10 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
   w.act = take(es * M * k * F);
   w.y = static_cast<float *>(take(sizeof(float) * kMaxDownSplits * M * k * d));
   w.gram = static_cast<double *>(take(sizeof(double) * N * (N + 3)));
+  const bool small = N <= kSelfMaxExperts && M <= kSelfMaxTokens;
+  w.partial = static_cast<double *>(take(small ? sizeof(double) * kMaxLogitSlices * M * N : 0));
+  w.list_count = static_cast<int32_t *>(take(sizeof(int32_t) * N));
+  w.lists = static_cast<int32_t *>(take(small ? sizeof(int32_t) * N * M : 0));
   w.bytes = off;
   return w;
 }
@@ -209,7 +217,19 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
                              float *y, int4 *items, bool items_ready, const int32_t *rank_count,
                              const int32_t *shortlist, int4 *pub_items, int32_t *pub_lists, hipStream_t st,
-                             void *const *trace = nullptr);
+                             void *const *trace = nullptr, const int32_t *lists = nullptr, int list_stride = 0);
+// The fused prologue of the layer call (prologue.hip): router projection on the fp64 matrix cores, then one
+// launch that leaves the shortlist (budget_ids), the restricted routing (tok_ids, tok_w) and, for every shortlist
+// rank r, the pairs routed to its expert (list_count[r]; lists[r * list_stride ..], flat ids t * k + slot, tokens
+// ascending).  partial: [logit_slices, M, N] doubles of scratch.  probs_out, scores_out, seg_expert, seg_off,
+// perm, n_loaded are optional copies for the caller (the last three cost one more small launch).
+bool fused_prologue_ok(const moespec_desc &ds, int M);
+int logit_slices(const moespec_desc &ds, int M);
+hipError_t launch_fused_prologue(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int B,
+                                 int policy, const int32_t *ext_shortlist, double *partial, double *probs_out,
+                                 double *scores_out, int32_t *budget_ids, int32_t *seg_expert, int32_t *tok_ids,
+                                 float *tok_w, int32_t *list_count, int32_t *lists, int list_stride,
+                                 int32_t *seg_off, int32_t *perm, int32_t *n_loaded, hipStream_t st);
 bool expert_ffn_self_segmenting(const moespec_desc &ds, int M);
 // Number of K-split copies of y that launch_expert_ffn writes for n_seg segments; out == NULL there skips
 // the combine and leaves the per-pair expert outputs in y.

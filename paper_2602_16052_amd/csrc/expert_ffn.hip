@@ -396,18 +396,22 @@ __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt
 // Called by every thread of the workgroup (it synchronises).  Returns the expert (-1: no work item) and the
 // number of work items.
 constexpr int kSelfMaxK = 16;
+// lists != NULL (the fused prologue has already written every shortlist rank's pairs, rank r at
+// lists + r * list_stride): nothing is collected, list receives the address of the piece inside that table.
 __device__ __forceinline__ int self_segment(const int32_t *__restrict__ rank_count,
                                             const int32_t *__restrict__ shortlist, int B,
                                             const int32_t *__restrict__ tok_ids, int M, int k, int tiles,
                                             int32_t *misc, int32_t *plist, int &m, int &item, int &tile,
-                                            int &n_items) {
+                                            int &n_items, const int32_t *__restrict__ lists, int list_stride,
+                                            const int32_t *&list) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int ids[kSelfMaxK];
   auto load_ids = [&](int t) {
 #pragma unroll
     for (int j = 0; j < kSelfMaxK; ++j) ids[j] = (j < k && t < M) ? tok_ids[(size_t)t * k + j] : -1;
   };
-  load_ids(tid);
+  list = plist;
+  if (!lists) load_ids(tid);
   const int c = tid < B ? rank_count[tid] : 0;
   const int ex = tid < B ? shortlist[tid] : -1;
   const int q = c > 0 ? piece_count(c) : 0;
@@ -433,6 +437,7 @@ __device__ __forceinline__ int self_segment(const int32_t *__restrict__ rank_cou
     misc[0] = ex;
     misc[5] = p * len;                 // the piece: pairs [lo, lo + m) of the expert's segment
     misc[6] = min(len, c - p * len);
+    misc[7] = tid;                     // its shortlist rank
   }
   __syncthreads();
   const int e = misc[0];
@@ -440,6 +445,10 @@ __device__ __forceinline__ int self_segment(const int32_t *__restrict__ rank_cou
   if (e < 0) return -1;
   const int lo = misc[5];
   m = misc[6];
+  if (lists) {
+    list = lists + (size_t)misc[7] * list_stride + lo;
+    return e;
+  }
   int base = 0;
   for (int t0 = 0; t0 < M && base < lo + m; t0 += kFfnThreads) {  // uniform trip count
     const int t = t0 + tid;
@@ -509,7 +518,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
     const int4 *__restrict__ items, const int32_t *__restrict__ perm, const int32_t *__restrict__ rank_count,
     const int32_t *__restrict__ shortlist, const int32_t *__restrict__ tok_ids, int n_seg, int cap, int M, int N,
     int k, int d, int F, long long perm_len, int4 *__restrict__ pub_items, int32_t *__restrict__ pub_lists,
-    uint16_t *__restrict__ act) {
+    const int32_t *__restrict__ lists, int list_stride, uint16_t *__restrict__ act) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
   __shared__ int32_t own_pairs[kPiecePairs];
   __shared__ int32_t misc[8];
@@ -518,7 +527,8 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
   const int32_t *plist;
   if (rank_count) {
     int n_items;
-    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_items);
+    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_items,
+                     lists, list_stride, plist);
     // The work items found here are published for the down pass (same table format as the budget stage's):
     // workgroup 0 writes the count, the first row tile of every item its entry and its pair list.
     if (pub_items && blockIdx.x == 0 && threadIdx.x == 0) pub_items[0] = int4{n_items, 0, 0, 0};
@@ -527,7 +537,6 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_gateup_lds_kernel(
       for (int p = threadIdx.x; p < m; p += kFfnThreads) pub_lists[(size_t)rank * kPiecePairs + p] = own_pairs[p];
       if (threadIdx.x == 0) pub_items[1 + rank] = int4{rank, e, rank * kPiecePairs, m};
     }
-    plist = own_pairs;
   } else {
     const int4 it = xcd_item(tiles, cap, items, tile, rank);
     e = it.y;
@@ -588,7 +597,7 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
     const uint16_t *__restrict__ act, const uint16_t *__restrict__ w_down, const int4 *__restrict__ items,
     const int32_t *__restrict__ perm, const int32_t *__restrict__ rank_count, const int32_t *__restrict__ shortlist,
     const int32_t *__restrict__ tok_ids, int n_seg, int cap, int M, int N, int k, int d, int F, int splits,
-    long long perm_len, float *__restrict__ y) {
+    long long perm_len, const int32_t *__restrict__ lists, int list_stride, float *__restrict__ y) {
   __shared__ __align__(16) unsigned char lds[kLdsBytes];
   __shared__ int32_t own_pairs[kPiecePairs];
   __shared__ int32_t misc[8];
@@ -599,9 +608,9 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_down_lds_kernel(
   const int32_t *plist;
   if (rank_count) {
     int n_items;
-    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_items);
+    e = self_segment(rank_count, shortlist, n_seg, tok_ids, M, k, tiles, misc, own_pairs, m, rank, tile, n_items,
+                     lists, list_stride, plist);
     if (e < 0 || e >= N || m <= 0 || m > kPiecePairs) return;
-    plist = own_pairs;
   } else {
     const int4 it = xcd_item(tiles, cap, items, tile, rank);
     e = it.y;
@@ -779,9 +788,10 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
                              float *y, int4 *items, bool items_ready, const int32_t *rank_count,
                              const int32_t *shortlist, int4 *pub_items, int32_t *pub_lists, hipStream_t st,
-                             void *const *trace) {
+                             void *const *trace, const int32_t *lists, int list_stride) {
   const int d = ds.d, F = ds.d_ff, k = ds.top_k;
   hipError_t e;
+  if (lists) pub_items = nullptr;  // every pass reads the prologue's lists: nothing to publish
   if (rank_count && !(shortlist && expert_ffn_self_segmenting(ds, M) && n_seg <= kFfnThreads)) rank_count = nullptr;
   if (!rank_count && !items_ready && !items) return hipErrorInvalidValue;
   const int cap = items_capacity(n_seg, M, k);  // work items of the LDS-tiled passes
@@ -804,7 +814,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
               static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(wt.w_gate),
               static_cast<const uint16_t *>(wt.w_up), items, perm, rank_count, shortlist, tok_ids, n_seg, cap, M,
               ds.n_experts, k, d, F, (long long)M * k, publish ? pub_items : nullptr, pub_lists,
-              static_cast<uint16_t *>(act));
+              rank_count ? lists : nullptr, list_stride, static_cast<uint16_t *>(act));
         } else {
           const int grid = xcd_grid(((d / 32 + kFfnWaves - 1) / kFfnWaves) * splits, cap);
           // after a self-segmenting gate/up pass the down pass reads the segments that pass has published
@@ -812,7 +822,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
               static_cast<const uint16_t *>(act), static_cast<const uint16_t *>(wt.w_down),
               publish ? pub_items : items, publish ? pub_lists : perm, publish ? nullptr : rank_count, shortlist,
               tok_ids, n_seg, cap, M, ds.n_experts, k, d, F, splits,
-              publish ? (long long)cap * kPiecePairs : (long long)M * k, y);
+              publish ? (long long)cap * kPiecePairs : (long long)M * k, rank_count ? lists : nullptr, list_stride, y);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         mark(pass - 1);
