@@ -28,6 +28,8 @@ Steps and the passages they follow
   oracle_ranking                  Eq. (6), "Oracle Ranking": greedy selection that minimises the
                                   reconstruction error against the gold output O*
   reconstruction_error            Section 4.5: ||O_S - O*||^2 / ||O*||^2, O* from Eq. (2)
+  rms_scale / layer_stack         the stack of layers joined by the residual stream (the layer-stack workload),
+                                  with the optional unit-RMS scaling of each layer's input
   segments                        the per-expert grouping of surviving
                                   (token, slot) pairs; defined here, the paper's
                                   batched matmul (Appendix C) hides it
@@ -415,17 +417,34 @@ def decision_margins(g, B: int, k: int, S: Optional[Sequence[int]] = None) -> Di
 
 
 # --------------------------------------------------------------------------- layer stack
-def layer_stack(h, layers, k: int, renorm: bool, B: int, policy: int, store_fn=None):
-    """Consecutive MoE layers joined by the residual connection: h <- h + MoE_S(h).
+def rms_scale(h) -> np.ndarray:
+    """x[t] = h[t] / sqrt(mean_j h[t, j]^2): every row scaled to unit root-mean-square (no learned gain)."""
+    h = _f64(h)
+    x = np.empty_like(h)
+    for t in range(h.shape[0]):
+        x[t] = h[t] / np.sqrt(np.dot(h[t], h[t]) / h.shape[1])
+    return x
 
-    ``layers`` yields one weight dict per layer.  ``store_fn`` (optional) rounds the
-    running hidden state to its storage format between layers.  Returns the final
-    hidden state and the per-layer results.
+
+def layer_stack(h, layers, k: int, renorm: bool, B: int, policy: int, store_fn=None, pre_norm: bool = False,
+                gate: str = SOFTMAX):
+    """Consecutive MoE layers joined by the residual connection: h <- h + MoE_S(x).
+
+    ``pre_norm=False``: x = h, the recurrence as the layer-stack workload words it.  ``pre_norm=True``: x = h scaled
+    row by row to unit root-mean-square (``rms_scale``) while the residual stream itself stays unscaled - the
+    stack driver's guard against the hidden scale squaring from layer to layer (a SwiGLU expert is quadratic in the
+    scale of its input).  ``layers`` yields one weight dict per layer.  ``store_fn`` (optional) rounds the MoE input
+    and the running hidden state to their storage format.  Returns the final hidden state and the per-layer results
+    (each with its MoE input under ``"x"``).
     """
     h = _f64(h)
     results = []
     for weights in layers:
-        r = layer_forward(h, weights, k, renorm, B, policy)
+        x = rms_scale(h) if pre_norm else h
+        if store_fn is not None:
+            x = _f64(store_fn(x))
+        r = layer_forward(x, weights, k, renorm, B, policy, gate=gate)
+        r["x"] = x
         results.append(r)
         h = h + r["out"]
         if store_fn is not None:

@@ -123,3 +123,34 @@ def test_layer_stack_adds_the_residual():
     h2 = h1 + O.layer_forward(h1, W1, k, True, B, O.SUBSTITUTE)["out"]
     np.testing.assert_array_equal(hL, h2)
     assert len(res) == 2
+
+
+def test_rms_scale_gives_unit_rms_rows_and_matches_torch():
+    rng = np.random.default_rng(3)
+    h = rng.standard_normal((7, 48)) * np.array([[0.01], [1.0], [30.0], [2.0], [5.0], [0.3], [1e3]])
+    x = O.rms_scale(h)
+    np.testing.assert_allclose(np.sqrt(np.mean(x * x, axis=1)), 1.0, rtol=1e-14)
+    ht = torch.from_numpy(h)
+    np.testing.assert_allclose(x, (ht / ht.pow(2).mean(dim=1, keepdim=True).sqrt()).numpy(), rtol=1e-14)
+    # scale invariance: a row and its multiple normalise to the same vector
+    np.testing.assert_allclose(O.rms_scale(h[1:2] * 37.5), x[1:2], rtol=1e-14)
+
+
+def test_layer_stack_with_pre_norm_feeds_scaled_rows_and_keeps_the_residual_unscaled():
+    N, d, Fdim, M, k, B = 4, 16, 24, 5, 2, 3
+    h, W0 = rand_layer(7, N, d, Fdim, M)
+    _, W1 = rand_layer(8, N, d, Fdim, M)
+    h = h * 3.0
+    hL, res = O.layer_stack(h, [W0, W1], k, True, B, O.TRUNCATE, pre_norm=True)
+    x0 = O.rms_scale(h)
+    h1 = h + O.layer_forward(x0, W0, k, True, B, O.TRUNCATE)["out"]
+    x1 = O.rms_scale(h1)
+    h2 = h1 + O.layer_forward(x1, W1, k, True, B, O.TRUNCATE)["out"]
+    np.testing.assert_array_equal(hL, h2)
+    np.testing.assert_array_equal(res[0]["x"], x0)
+    np.testing.assert_array_equal(res[1]["x"], x1)
+    # the storage hook is applied to the MoE input and to the running state
+    rounded = lambda a: np.round(a * 64.0) / 64.0
+    hS, resS = O.layer_stack(h, [W0], k, True, B, O.TRUNCATE, store_fn=rounded, pre_norm=True)
+    np.testing.assert_array_equal(resS[0]["x"], rounded(x0))
+    np.testing.assert_array_equal(hS, rounded(h + O.layer_forward(rounded(x0), W0, k, True, B, O.TRUNCATE)["out"]))
