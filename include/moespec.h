@@ -228,6 +228,31 @@ moespec_status moespec_layer_forward_static(const moespec_desc *desc, const moes
                                             const void *residual, void *out, void *hip_stream);
 
 /*
+ * The layer stack of the coarse-expert workload: n_layers consecutive MoE layers joined by the residual stream.
+ * For l = 0 .. n_layers-1:  x = pre_norm ? rms_scale(h) : h;  h <- h + MoE_S(x) with layer l's weights, every
+ * layer being Algorithm 1 as in moespec_layer_forward (Section 3.3 notes that a token without a surviving expert
+ * passes through on the residual connection alone).  pre_norm = 1 scales every row of the layer input to unit
+ * root-mean-square (moespec_rms_scale) and leaves the residual stream itself unscaled; pre_norm = 0 is the plain
+ * recurrence.
+ *   layers     HOST array of n_layers moespec_weights (device pointers inside), 1 <= n_layers <= 4096
+ *   h          [M, d] dtype  in/out  residual stream, updated in place
+ *   budget_ids [n_layers, B] int32 out (may be NULL)  every layer's shortlist in rank order
+ *   tok_ids    [n_layers, M, k] int32 out (may be NULL)  every layer's restricted routing
+ * All layers share desc, B, policy and the workspace (size rule as for the other calls).
+ */
+moespec_status moespec_stack_forward(const moespec_desc *desc, const moespec_weights *layers, int32_t n_layers,
+                                     void *h, int32_t M, int32_t B, int32_t policy, int32_t pre_norm,
+                                     int32_t *budget_ids, int32_t *tok_ids,
+                                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * x[t] = h[t] / sqrt(mean_j h[t, j]^2) for every row (fp32 arithmetic, fixed summation order): the input scaling
+ * of moespec_stack_forward with pre_norm = 1, exported so that a stack can also be driven layer by layer.
+ *   h, x [M, d] dtype (device); x may be the same buffer as h.  No workspace.
+ */
+moespec_status moespec_rms_scale(const moespec_desc *desc, const void *h, int32_t M, void *x, void *hip_stream);
+
+/*
  * Static ranking - Eq. (4): c_i = number of calibration tokens h with i in T_k(h).
  *   topk_ids [M, k] int32  in     natural top-k ids of a batch of calibration tokens (moespec_route);
  *                                 entries outside [0, N) are ignored

@@ -25,7 +25,7 @@ GATE_SOFTMAX, GATE_SIGMOID = 0, 1
 
 EXPORTS = ("moespec_abi_version", "moespec_status_string", "moespec_check_desc", "moespec_workspace_bytes",
            "moespec_route", "moespec_budget", "moespec_expert_ffn", "moespec_layer_forward",
-           "moespec_layer_forward_static",
+           "moespec_layer_forward_static", "moespec_stack_forward", "moespec_rms_scale",
            "moespec_calibration_count", "moespec_static_shortlist", "moespec_coverage_curve",
            "moespec_reconstruction_error", "moespec_oracle_ranking", "moespec_stream_read")
 
@@ -94,6 +94,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moespec_layer_forward_static.restype = c_int32
     lib.moespec_layer_forward_static.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_int32,
                                                  c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.moespec_stack_forward.restype = c_int32
+    lib.moespec_stack_forward.argtypes = [POINTER(Desc), POINTER(Weights), c_int32, c_void_p, c_int32, c_int32, c_int32,
+                                          c_int32, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.moespec_rms_scale.restype = c_int32
+    lib.moespec_rms_scale.argtypes = [POINTER(Desc), c_void_p, c_int32, c_void_p, c_void_p]
     lib.moespec_calibration_count.restype = c_int32
     lib.moespec_calibration_count.argtypes = [POINTER(Desc), c_void_p, c_int32, c_void_p, c_void_p]
     lib.moespec_static_shortlist.restype = c_int32
@@ -351,6 +356,53 @@ def moespec_layer_forward(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: 
         _stream(stream))
     _check(st, "moespec_layer_forward")
     return (out, tap_t) if taps else out
+
+
+def moespec_rms_scale(desc: LayerDesc, h: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """x[t] = h[t] / rms(h[t]) (the input scaling of the layer stack).  Returns x[M, d] in the layer dtype."""
+    M, dt = h.shape[0], desc.torch_dtype
+    if out is None:
+        out = torch.empty_like(h)
+    cd = desc.c()
+    st = load_library().moespec_rms_scale(ctypes.byref(cd), _ptr(h, dt, M * desc.d, "h"), M,
+                                          _ptr(out, dt, M * desc.d, "x"), _stream(stream))
+    _check(st, "moespec_rms_scale")
+    return out
+
+
+class StackForwardCall:
+    """moespec_stack_forward with its arguments marshalled once (h is updated in place on every call)."""
+
+    def __init__(self, desc: LayerDesc, layers, h: torch.Tensor, B: int, policy: int, ws: torch.Tensor,
+                 pre_norm: bool = True, budget_ids: Optional[torch.Tensor] = None,
+                 tok_ids: Optional[torch.Tensor] = None, stream=None):
+        M, dt, L = h.shape[0], desc.torch_dtype, len(layers)
+        self._keep = (layers, h, ws, budget_ids, tok_ids)
+        self._fn = load_library().moespec_stack_forward
+        self._cd = desc.c()
+        self._cw = (Weights * L)(*[_weights(desc, w, True, True) for w in layers])
+        self._args = (ctypes.byref(self._cd), self._cw, L, _ptr(h, dt, M * desc.d, "h"), M, int(B), int(policy),
+                      int(bool(pre_norm)), _ptr(budget_ids, torch.int32, L * max(int(B), 1), "budget_ids"),
+                      _ptr(tok_ids, torch.int32, L * M * desc.top_k, "tok_ids"), _ptr(ws), ws.numel(), _stream(stream))
+
+    def __call__(self):
+        st = self._fn(*self._args)
+        if st != OK:
+            raise MoeSpecError(int(st), "moespec_stack_forward")
+
+
+def moespec_stack_forward(desc: LayerDesc, layers, h: torch.Tensor, B: int, policy: int, ws: torch.Tensor,
+                          pre_norm: bool = True, taps: bool = False, stream=None):
+    """The layer stack h <- h + MoE_S(x) over ``layers`` (a list of weight dicts), in place on ``h``.
+    Returns ``h`` or, with ``taps=True``, ``(h, dict(budget_ids[L, B], tok_ids[L, M, k]))``."""
+    L, M = len(layers), h.shape[0]
+    tap = None
+    if taps:
+        i32 = dict(dtype=torch.int32, device=h.device)
+        tap = dict(budget_ids=torch.empty((L, max(int(B), 1)), **i32), tok_ids=torch.empty((L, M, desc.top_k), **i32))
+    StackForwardCall(desc, layers, h, B, policy, ws, pre_norm, tap["budget_ids"] if tap else None,
+                     tap["tok_ids"] if tap else None, stream)()
+    return (h, tap) if taps else h
 
 
 STATIC_SCRATCH_BYTES = 48 << 20

@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libmoespec.so")
-SOURCES = ("api.hip", "route.hip", "budget.hip", "prologue.hip", "expert_ffn.hip", "analysis.hip")
+SOURCES = ("api.hip", "route.hip", "budget.hip", "prologue.hip", "expert_ffn.hip", "analysis.hip", "stack.hip")
 
 # Packed-FP32 instructions are disabled for all device code (hipcc's host pass warns that it does
 # not know the feature; that warning is harmless).

@@ -149,7 +149,7 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
 
 extern "C" {
 
-int32_t moespec_abi_version(void) { return 3; }
+int32_t moespec_abi_version(void) { return 4; }
 
 const char *moespec_status_string(int32_t status) {
   switch (status) {
@@ -234,6 +234,40 @@ moespec_status moespec_layer_forward_static(const moespec_desc *desc, const moes
   if (!ws) return MOESPEC_ERR_HIP;
   return layer_forward(desc, weights, h, M, B, policy, ext_shortlist, residual, out, nullptr, ws, (size_t)MOESPEC_STATIC_SCRATCH_BYTES,
                        hip_stream);
+}
+
+moespec_status moespec_rms_scale(const moespec_desc *desc, const void *h, int32_t M, void *x, void *hip_stream) {
+  moespec_status s = check_desc(desc);
+  if (s != MOESPEC_OK) return s;
+  if (M < 1 || M > kMaxTokens || !h || !x || !aligned16(h) || !aligned16(x)) return MOESPEC_ERR_INVALID_ARG;
+  return from_hip(launch_rms_scale(*desc, h, M, x, static_cast<hipStream_t>(hip_stream)));
+}
+
+moespec_status moespec_stack_forward(const moespec_desc *desc, const moespec_weights *layers, int32_t n_layers, void *h,
+                                     int32_t M, int32_t B, int32_t policy, int32_t pre_norm, int32_t *budget_ids,
+                                     int32_t *tok_ids, void *ws, size_t ws_bytes, void *hip_stream) {
+  moespec_status s = check_common(desc, M, ws, ws_bytes);
+  if (s != MOESPEC_OK) return s;
+  if (!layers || n_layers < 1 || n_layers > 4096 || (pre_norm != 0 && pre_norm != 1)) return MOESPEC_ERR_INVALID_ARG;
+  for (int32_t l = 0; l < n_layers; ++l)  // every layer is validated before the first launch
+    if ((s = check_layer_args(desc, &layers[l], h, B, policy, h, h)) != MOESPEC_OK) return s;
+  Workspace w = carve_workspace(*desc, M, ws);
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const void *x = h;
+    if (pre_norm) {
+      if (launch_rms_scale(*desc, h, M, w.xnorm, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return MOESPEC_ERR_HIP;
+      x = w.xnorm;
+    }
+    moespec_taps t{};
+    t.budget_ids = budget_ids ? budget_ids + (size_t)l * B : nullptr;
+    t.tok_ids = tok_ids ? tok_ids + (size_t)l * M * desc->top_k : nullptr;
+    // the combine reads residual[t, j] and writes out[t, j] in the same thread, after every kernel that reads the
+    // layer input: updating the residual stream in place is safe
+    if ((s = layer_forward(desc, &layers[l], x, M, B, policy, nullptr, h, h, &t, ws, ws_bytes, hip_stream)) != MOESPEC_OK)
+      return s;
+  }
+  return MOESPEC_OK;
 }
 
 moespec_status moespec_calibration_count(const moespec_desc *desc, const int32_t *topk_ids, int32_t M,

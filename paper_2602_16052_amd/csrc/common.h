@@ -149,6 +149,7 @@ struct Workspace {
   double *partial;    // [kMaxLogitSlices, M, N] partial router projections of the fused prologue
   int32_t *list_count;  // [N] pairs per shortlist rank (fused prologue)
   int32_t *lists;     // [N, M] their pair lists (only for shapes the fused prologue covers)
+  void *xnorm;        // [M, d] dtype: the scaled layer input of the layer stack
   size_t bytes;
 };
 
@@ -185,6 +186,7 @@ inline Workspace carve_workspace(const moespec_desc &ds, int64_t M, void *base) 
   w.partial = static_cast<double *>(take(small ? sizeof(double) * kMaxLogitSlices * M * N : 0));
   w.list_count = static_cast<int32_t *>(take(sizeof(int32_t) * N));
   w.lists = static_cast<int32_t *>(take(small ? sizeof(int32_t) * N * M : 0));
+  w.xnorm = take(es * M * d);
   w.bytes = off;
   return w;
 }
@@ -243,6 +245,8 @@ hipError_t launch_coverage_curve(const double *scores, int N, double *curve, hip
 hipError_t launch_oracle_ranking(const moespec_desc &ds, const float *y, int splits, size_t split_stride,
                                  const int32_t *tok_ids, const float *tok_w, int M, int B, double *pair_gram,
                                  double *gram, int32_t *ranking, double *err, hipStream_t st);
+// x[t] = h[t] / rms(h[t]) (stack.hip); x may alias h.
+hipError_t launch_rms_scale(const moespec_desc &ds, const void *h, int M, void *x, hipStream_t st);
 hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *checksum, hipStream_t st);
 hipError_t launch_reconstruction_error(const moespec_desc &ds, const void *out_budgeted, const void *out_full, int M,
                                        double *part, double *err, hipStream_t st);

@@ -311,9 +311,13 @@ constexpr int kLdsBytes = 65536;  // 32 KB of wave-private weight tiles + token 
 // tiles (row stride K elements).  xbase + xsrc[q] bytes: this lane's source row (already at its 16-byte piece)
 // for its q-th share of the token tile.  Accumulates acc0[j] (tile 0) and acc1[j] (tile 1) over the K range
 // [kb, kb + kl) of the rows (row stride K).
-template <int NT, int U>
+// make_xsrc(xsrc) fills the token-row offsets from the pair ids the caller has ALREADY loaded into registers; it is
+// called after the weight loads of the first chunk have been issued.  Loads complete in issue order, so the wait for
+// the (earlier issued) pair ids leaves those weight loads in flight: the expert's first bytes are on their way while
+// the token rows are still being looked up.
+template <int NT, int U, class XF>
 __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt1, int K, int kb, int kl, int ks,
-                                         const uint16_t *xbase, const uint32_t (&xsrc)[NT * U / 4], unsigned char *lds,
+                                         const uint16_t *xbase, XF make_xsrc, unsigned char *lds,
                                          f32x4 (&acc0)[NT], f32x4 (&acc1)[NT]) {
   using C = Chunk<U>;
   constexpr int IPW = NT * U / 4;  // token-tile loads per wave per chunk (4 waves share the tile)
@@ -330,15 +334,22 @@ __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt
   const int lrow = lane / C::CPR, lpc = lane % C::CPR;
   const uint32_t lane_off = 2u * ((uint32_t)lrow * (uint32_t)K + (uint32_t)lpc * 8u);
   bf16x8 GA[2][U], GX[IPW];
-  auto issue = [&](int k) {
+  uint32_t xsrc[IPW];
+  auto issue_w = [&](int k) {
 #pragma unroll
     for (int q = 0; q < U; ++q) {
       const uint32_t off = lane_off + 2u * ((uint32_t)(q * C::RPI) * (uint32_t)K + (uint32_t)k);
       GA[0][q] = ld_stream(at_bytes(wt0, off));
       GA[1][q] = ld_stream(at_bytes(wt1, off));
     }
+  };
+  auto issue_x = [&](int k) {
 #pragma unroll
     for (int q = 0; q < IPW; ++q) GX[q] = ld_frag(at_bytes(xbase, xsrc[q] + 2u * (uint32_t)k));
+  };
+  auto issue = [&](int k) {
+    issue_w(k);
+    issue_x(k);
   };
   auto park = [&](int buf) {
 #pragma unroll
@@ -373,7 +384,10 @@ __device__ __forceinline__ void lds_pass(const uint16_t *wt0, const uint16_t *wt
   // ks elements into that range and wrapping inside it
   const int nst = kl / C::KC;
   int k = ((ks % kl) / C::KC) * C::KC;
-  issue(kb + k);
+  issue_w(kb + k);
+  __builtin_amdgcn_sched_barrier(0);  // keep the weight loads ahead of the wait for the pair ids
+  make_xsrc(xsrc);
+  issue_x(kb + k);
   for (int i = 0; i < nst; ++i) {
     park(kDoubleX ? (i & 1) : 0);
     k += C::KC;
@@ -484,18 +498,27 @@ __device__ __forceinline__ void gateup_lds(const uint16_t *wt0, const uint16_t *
   using C = Chunk<U>;
   constexpr int IPW = NT * U / 4;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  uint32_t xsrc[IPW];  // 32-bit byte offsets: M * d < 2^31 elements (checked on the host)
+  int pair[IPW];  // this lane's pair ids, loaded now and turned into row offsets inside lds_pass
 #pragma unroll
   for (int q = 0; q < IPW; ++q) {
     const int g = (wave * IPW + q) * 64 + lane;
     int p = c0 + g / C::CPR;
     p = p < m ? p : m - 1;  // pad rows repeat the last token; their columns are never stored
-    xsrc[q] = 2u * ((uint32_t)(pair_at(plist, p, n_pairs) / k) * (uint32_t)d + (uint32_t)(g % C::CPR) * 8u);
+    pair[q] = plist[p];
   }
+  // 32-bit byte offsets: M * d < 2^31 elements (checked on the host)
+  auto make_xsrc = [&](uint32_t (&xsrc)[IPW]) {
+#pragma unroll
+    for (int q = 0; q < IPW; ++q) {
+      const int g = (wave * IPW + q) * 64 + lane;
+      const int pr = pair[q] < 0 ? 0 : (pair[q] >= n_pairs ? n_pairs - 1 : pair[q]);
+      xsrc[q] = 2u * ((uint32_t)(pr / k) * (uint32_t)d + (uint32_t)(g % C::CPR) * 8u);
+    }
+  };
   f32x4 accg[NT], accu[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) accg[j] = accu[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  lds_pass<NT, U>(wt0, wt1, d, 0, d, ks, h, xsrc, lds, accg, accu);
+  lds_pass<NT, U>(wt0, wt1, d, 0, d, ks, h, make_xsrc, lds, accg, accu);
   const int col = lane & 15, kg = lane >> 4;
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
@@ -569,18 +592,27 @@ __device__ __forceinline__ void down_lds(const uint16_t *wt0, const uint16_t *wt
   using C = Chunk<U>;
   constexpr int IPW = NT * U / 4;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  uint32_t xsrc[IPW];  // 32-bit byte offsets: M * k * F < 2^31 elements (checked on the host)
+  int pair[IPW];  // this lane's pair ids, loaded now and turned into row offsets inside lds_pass
 #pragma unroll
   for (int q = 0; q < IPW; ++q) {
     const int g = (wave * IPW + q) * 64 + lane;
     int p = c0 + g / C::CPR;
     p = p < m ? p : m - 1;
-    xsrc[q] = 2u * ((uint32_t)pair_at(plist, p, n_pairs) * (uint32_t)F + (uint32_t)(g % C::CPR) * 8u);
+    pair[q] = plist[p];
   }
+  // 32-bit byte offsets: M * k * F < 2^31 elements (checked on the host)
+  auto make_xsrc = [&](uint32_t (&xsrc)[IPW]) {
+#pragma unroll
+    for (int q = 0; q < IPW; ++q) {
+      const int g = (wave * IPW + q) * 64 + lane;
+      const int pr = pair[q] < 0 ? 0 : (pair[q] >= n_pairs ? n_pairs - 1 : pair[q]);
+      xsrc[q] = 2u * ((uint32_t)pr * (uint32_t)F + (uint32_t)(g % C::CPR) * 8u);
+    }
+  };
   f32x4 acc0[NT], acc1[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) acc0[j] = acc1[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  lds_pass<NT, U>(wt0, wt1, F, kb, kl, ks, act, xsrc, lds, acc0, acc1);
+  lds_pass<NT, U>(wt0, wt1, F, kb, kl, ks, act, make_xsrc, lds, acc0, acc1);
   const int col = lane & 15, kg = lane >> 4;
 #pragma unroll
   for (int j = 0; j < NT; ++j) {

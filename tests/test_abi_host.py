@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert mb.abi_version() == 3
+    assert mb.abi_version() == 4
     assert mb.status_string(mb.OK) == "ok"
     assert "workspace" in mb.status_string(mb.ERR_WORKSPACE_TOO_SMALL)
     assert mb.status_string(99) == "unknown status"
@@ -203,3 +203,25 @@ def test_binding_refuses_cpu_tensors(lib):
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(FileNotFoundError):
         mb.load_library(str(tmp_path / "nope.so"))
+
+
+def test_stack_calls_reject_bad_arguments(lib):
+    d = D()
+    cd = d.c()
+    wsb = mb.workspace_bytes(d, 8)
+    P = 0x50000
+    two = (mb.Weights * 2)(mb.Weights(P, None, P, P, P), mb.Weights(P, None, P, P, P))
+    f = lib.moespec_stack_forward
+    assert f(ctypes.byref(cd), two, 0, P, 8, 8, mb.SUBSTITUTE, 1, None, None, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    assert f(ctypes.byref(cd), None, 2, P, 8, 8, mb.SUBSTITUTE, 1, None, None, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    assert f(ctypes.byref(cd), two, 2, None, 8, 8, mb.SUBSTITUTE, 1, None, None, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    assert f(ctypes.byref(cd), two, 2, P, 8, 8, mb.SUBSTITUTE, 2, None, None, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    assert f(ctypes.byref(cd), two, 2, P, 8, 3, mb.SUBSTITUTE, 1, None, None, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    assert f(ctypes.byref(cd), two, 2, P, 8, 8, mb.SUBSTITUTE, 1, None, None, 0x10000, 64,
+             None) == mb.ERR_WORKSPACE_TOO_SMALL
+    bad = (mb.Weights * 2)(mb.Weights(P, None, P, P, P), mb.Weights(P, None, None, P, P))   # second layer incomplete
+    assert f(ctypes.byref(cd), bad, 2, P, 8, 8, mb.SUBSTITUTE, 1, None, None, 0x10000, wsb, None) == mb.ERR_INVALID_ARG
+    g = lib.moespec_rms_scale
+    assert g(ctypes.byref(cd), None, 8, P, None) == mb.ERR_INVALID_ARG
+    assert g(ctypes.byref(cd), P, 0, P, None) == mb.ERR_INVALID_ARG
+    assert g(ctypes.byref(cd), P, 8, P + 4, None) == mb.ERR_INVALID_ARG

@@ -142,65 +142,183 @@ def test_budget_invariants_at_full_size(full_case):
 
 # ---------------------------------------------------------------------------------------------- layer stack
 STACK = wl.CONFIGS["coarse_stack"]
+STACK_RUN = (4, mb.SUBSTITUTE)     # budget and policy with which the residual stream is advanced
+
+
+def bf16_round(a: np.ndarray) -> np.ndarray:
+    """float64 -> nearest bfloat16 value, as float32 (the storage rounding of the stack's hidden state)."""
+    return wl.as_f32(wl.round_to_bf16_bits(np.asarray(a, dtype=np.float32)))
 
 
 @pytest.fixture(scope="module")
-def stack_state():
-    """Hidden state carried from layer to layer by the GPU path (teacher forcing for the oracle)."""
-    h = wl.hidden_states(STACK)
-    return dict(h_d=to_device(h), layer=0, desc=desc_of(STACK), ws=mb.alloc_workspace(desc_of(STACK), STACK.M))
+def stack():
+    """The 8 coarse layers: weights drawn layer by layer on first use and kept (host bits and device tensors), the
+    hidden state the GPU path carries from layer to layer, and the inputs it saw."""
+    cfg = STACK
+    desc = desc_of(cfg)
+    st = dict(cfg=cfg, desc=desc, ws=mb.alloc_workspace(desc, cfg.M), host={}, dev={}, h0=wl.hidden_states(cfg),
+              layer=0, seen_h=[], margins=[])
+    st["h_d"] = to_device(st["h0"])
+
+    def weights(layer):
+        if layer not in st["host"]:
+            t0 = time.time()
+            st["host"][layer] = wl.layer_weights(cfg, layer=layer, threads=16)
+            st["dev"][layer] = upload_weights(st["host"][layer])
+            print(f"[stack layer {layer}] drew and uploaded 8 experts in {time.time() - t0:.1f}s", flush=True)
+        return st["host"][layer], st["dev"][layer]
+
+    st["weights"] = weights
+    yield st
+    st["host"].clear()
+    st["dev"].clear()
+    torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("layer", range(STACK.n_layers))
-def test_coarse_stack_layer(stack_state, layer):
-    """Layer `layer` of the 8-layer stack h <- h + MoE_S(x), x = h / rms(h), B=4, substitution, fed with the
-    hidden state the GPU path itself produced for the previous layers (teacher forcing: the oracle gets the
-    same bf16 input bits).  Routing of every budget and both policies is checked against the oracle on that
-    input; outputs on sampled tokens.
-
-    The unit-RMS scaling of the MoE input is scaffolding of this stack driver, not a step of the method: with
-    N(0, 0.02) weights at d=4096, F=14336 the plain recurrence h <- h + MoE(h) squares the hidden scale every
-    layer (measured output scales 8.5, 52, 1817, then overflow; routing probabilities underflow to 0/0)."""
-    cfg, st = STACK, stack_state
+def test_coarse_stack_layer_teacher_forced(stack, layer):
+    """Layer `layer` of the stack h <- h + MoE_S(x), x = rms_scale(h), fed with the hidden state the GPU path itself
+    produced for the layers before (teacher forcing: the oracle reads the same bf16 bits of x).  For every budget of
+    the sweep and both policies: routing bit-exact and outputs within tolerance for every token, and the decision
+    margins of this layer's router on its actual input.  Outputs reach several units here, where half a bf16 ulp is already 0.0156:
+    the absolute bound scales with max|oracle| (scale_aware)."""
+    cfg, st = STACK, stack
     assert st["layer"] == layer, "stack layers must run in order"
-    B_run, sample = 4, [0, cfg.M - 1]
+    W, W_d = st["weights"](layer)
     res_d = st["h_d"]
-    hf = res_d.float()
-    h_d = (hf / hf.pow(2).mean(dim=1, keepdim=True).sqrt()).to(torch.bfloat16)
-    h_o = h_d.float().cpu().numpy()
-    router = wl.layer_weights(cfg, layer=layer, experts=())
-    W_o = dict(w_router=wl.as_f32(router["w_router"]), b_router=router["b_router"])
-    ref = routing_reference(cfg, h_o, W_o, B_run, mb.SUBSTITUTE)
-    t0 = time.time()
-    W = wl.layer_weights(cfg, layer=layer, experts=tuple(int(e) for e in sorted(ref["S"])), threads=16)
-    print(f"[stack layer {layer}] generated {B_run} experts in {time.time() - t0:.1f}s", flush=True)
-    W_d = upload_weights(W)
-    # routing for every budget / policy needs no expert weights beyond the router
+    st["seen_h"].append(res_d.clone())
+    x_d = mb.moespec_rms_scale(st["desc"], res_d)
+    torch.cuda.synchronize()
+    # the scaling itself: fp32 on the GPU against fp64 in the oracle, both rounded to bf16 (1 ulp = 2^-8 relative)
+    x_o = x_d.float().cpu().numpy()
+    want_x = O.rms_scale(res_d.float().cpu().numpy())
+    assert np.max(np.abs(x_o - want_x) / np.maximum(np.abs(want_x), 1e-3)) <= 2.0 ** -8
+    W_o = dict(w_router=wl.as_f32(W["w_router"]), b_router=W["b_router"])
+    wide = {}
+
+    def widened(e):   # fp64 copies, made once per layer: the oracle then uses them as they are
+        if e not in wide:
+            wide[e] = {key: wl.as_f32(W[key][e]).astype(np.float64) for key in ("w_gate", "w_up", "w_down")}
+        return wide[e]
+
     for B in cfg.budgets:
         for policy in (mb.TRUNCATE, mb.SUBSTITUTE):
-            r = mb.moespec_route(st["desc"], W_d, h_d, st["ws"])
-            b = mb.moespec_budget(st["desc"], r["probs"], B, policy, st["ws"])
+            ref = routing_reference(cfg, x_o, W_o, B, policy)
+            m = O.decision_margins(ref["probs"], B, cfg.top_k, list(ref["S"]))
+            assert min(m["topk"], m["score"], m["sub"] if B >= cfg.top_k else 1.0) > 1e-9, (layer, B, m)
+            out, taps = mb.moespec_layer_forward(st["desc"], W_d, x_d, B, policy, st["ws"], taps=True)
             torch.cuda.synchronize()
-            rr = routing_reference(cfg, h_o, W_o, B, policy)
-            assert np.array_equal(b["budget_ids"].cpu().numpy()[:B], rr["S"])
-            assert np.array_equal(b["tok_ids"].cpu().numpy(), rr["tok_ids"])
-            assert np.array_equal(b["seg_off"].cpu().numpy()[:B + 1], rr["seg_off"])
-            assert np.array_equal(b["perm"].cpu().numpy()[:int(rr["seg_off"][-1])], rr["perm"])
-    moe, taps = mb.moespec_layer_forward(st["desc"], W_d, h_d, B_run, mb.SUBSTITUTE, st["ws"], taps=True)
-    nxt = mb.moespec_layer_forward(st["desc"], W_d, h_d, B_run, mb.SUBSTITUTE, st["ws"], residual=res_d)
+            assert_routing_equal(taps, ref, B)
+            every = (B, policy) == STACK_RUN
+            sample = list(range(cfg.M))
+            need = sorted({int(e) for t in sample for e in ref["tok_ids"][t] if e >= 0})
+            Wexp = {key: {e: widened(e)[key] for e in need} for key in ("w_gate", "w_up", "w_down")}
+            t0 = time.time()
+            want = O.combine(x_o, ref["tok_ids"], ref["tok_w"], Wexp["w_gate"], Wexp["w_up"], Wexp["w_down"],
+                             tokens=sample)
+            err, scale = assert_out_close(out_to_numpy(out), want, cfg.dtype, rows=sample, scale_aware=True,
+                                          what=f"stack layer {layer} B={B} policy={policy}")
+            print(f"[stack layer {layer}] B={B} policy={policy}: {len(sample)} tokens, max|diff| {err:.3e} at scale "
+                  f"{scale:.2f}, oracle {time.time() - t0:.1f}s", flush=True)
+            if every:
+                want_run = want
+    # advance the residual stream: h + MoE_S(x), stored in bf16 (half an ulp of the stored value on top of the MoE
+    # tolerance)
+    B_run, policy_run = STACK_RUN
+    nxt = mb.moespec_layer_forward(st["desc"], W_d, x_d, B_run, policy_run, st["ws"], residual=res_d)
     torch.cuda.synchronize()
-    assert_routing_equal(taps, ref, B_run)
-    need = sorted({int(e) for t in sample for e in ref["tok_ids"][t]})
-    Wexp = {key: {e: wl.as_f32(W[key][e]) for e in need} for key in ("w_gate", "w_up", "w_down")}
-    want = O.combine(h_o, ref["tok_ids"], ref["tok_w"], Wexp["w_gate"], Wexp["w_up"], Wexp["w_down"], tokens=sample)
-    err, scale = assert_out_close(out_to_numpy(moe), want, cfg.dtype, rows=sample, scale_aware=True,
-                                  what=f"stack layer {layer} MoE output")
-    print(f"[stack layer {layer}] max|diff| {err:.3e} at output scale {scale:.2f}", flush=True)
-    # residual stream: h + MoE(h), stored in bf16 (half an ulp of the stored value on top of the MoE tolerance)
-    got_h = out_to_numpy(nxt)[sample]
-    want_h = res_d.float().cpu().numpy()[sample].astype(np.float64) + want[sample]
+    got_h = out_to_numpy(nxt)
+    want_h = res_d.float().cpu().numpy().astype(np.float64) + want_run
+    scale = float(np.max(np.abs(want_run)))
+    assert np.all(np.isfinite(got_h))
     assert np.all(np.abs(got_h - want_h) <= 2e-2 * max(1.0, scale) + 2.0 ** -8 * np.abs(want_h))
-    assert np.all(np.isfinite(out_to_numpy(nxt)))
     st["h_d"], st["layer"] = nxt, layer + 1
-    del W_d, W
-    torch.cuda.empty_cache()
+
+
+def test_coarse_stack_call_equals_the_layer_by_layer_run(stack):
+    """moespec_stack_forward over the 8 layers in one call reproduces, bit for bit, the hidden state that the
+    layer-by-layer run above arrived at, and its taps name the same routing."""
+    cfg, st = STACK, stack
+    assert st["layer"] == cfg.n_layers, "runs after the per-layer tests"
+    layers = [st["weights"](l)[1] for l in range(cfg.n_layers)]
+    h = to_device(st["h0"])
+    B_run, policy_run = STACK_RUN
+    h, taps = mb.moespec_stack_forward(st["desc"], layers, h, B_run, policy_run, st["ws"], pre_norm=True, taps=True)
+    torch.cuda.synchronize()
+    assert torch.equal(h, st["h_d"])
+    for l in (0, cfg.n_layers - 1):
+        x = mb.moespec_rms_scale(st["desc"], st["seen_h"][l])
+        _, t = mb.moespec_layer_forward(st["desc"], layers[l], x, B_run, policy_run, st["ws"], taps=True)
+        torch.cuda.synchronize()
+        assert torch.equal(t["budget_ids"][:B_run], taps["budget_ids"][l]) and torch.equal(t["tok_ids"], taps["tok_ids"][l])
+
+
+def test_coarse_stack_free_running_against_the_oracle(stack):
+    """Both sides run all 8 layers on their own from the same h_0 (no teacher forcing): the oracle's stack in fp64 with
+    the hidden state and every layer input rounded to bf16 as the GPU stores them.  A near-tie downstream may
+    legitimately route differently once the two hidden states differ in their last bits, so routing differences are
+    counted and reported, and the gate is the final hidden state."""
+    cfg, st = STACK, stack
+    assert st["layer"] == cfg.n_layers, "runs after the per-layer tests"
+    B_run, policy_run = STACK_RUN
+
+    def oracle_layers():
+        for l in range(cfg.n_layers):
+            W = st["weights"](l)[0]
+            yield dict(w_router=wl.as_f32(W["w_router"]), b_router=W["b_router"],
+                       **{key: _LazyF64(W[key]) for key in ("w_gate", "w_up", "w_down")})
+
+    t0 = time.time()
+    h_ref, results = O.layer_stack(wl.as_f32(st["h0"]), oracle_layers(), cfg.top_k, cfg.renorm, B_run, policy_run,
+                                   store_fn=bf16_round, pre_norm=True)
+    print(f"[stack free-running] oracle took {time.time() - t0:.1f}s", flush=True)
+    layers = [st["weights"](l)[1] for l in range(cfg.n_layers)]
+    h, taps = mb.moespec_stack_forward(st["desc"], layers, to_device(st["h0"]), B_run, policy_run, st["ws"],
+                                       pre_norm=True, taps=True)
+    torch.cuda.synchronize()
+    got_ids = [taps["tok_ids"][l].cpu().numpy() for l in range(cfg.n_layers)]
+    flips = [int(np.sum(got_ids[l] != results[l]["tok_ids"])) for l in range(cfg.n_layers)]
+    shortlist_diffs = [int(np.sum(taps["budget_ids"][l].cpu().numpy() != results[l]["S"])) for l in range(cfg.n_layers)]
+    got = out_to_numpy(h)
+    # a token's hidden state depends on the other tokens only through the shortlists: with equal shortlists in every
+    # layer, a token that was routed identically in every layer must agree with the oracle within tolerance
+    same_path = np.all([np.all(got_ids[l] == results[l]["tok_ids"], axis=1) for l in range(cfg.n_layers)], axis=0)
+    if any(shortlist_diffs):
+        first = next(l for l, n in enumerate(shortlist_diffs) if n)
+        print(f"[stack free-running] shortlists differ from layer {first} on: outputs are reported, not gated", flush=True)
+        same_path[:] = False
+    scale = float(np.max(np.abs(h_ref)))
+    err_all = float(np.max(np.abs(got - h_ref)))
+    err_same = float(np.max(np.abs(got[same_path] - h_ref[same_path]))) if same_path.any() else 0.0
+    print(f"[stack free-running] routing slots that differ per layer {flips}, shortlist entries {shortlist_diffs}; "
+          f"{int(same_path.sum())} of {cfg.M} tokens routed identically in all layers; final hidden state max|diff| "
+          f"{err_same:.3e} on those ({err_all:.3e} on all) at scale {scale:.2f}", flush=True)
+    assert np.all(np.isfinite(got))
+    # every routing difference must be a genuine near-tie in the oracle's own probabilities: at the first layer where
+    # a token differs, the two sides' inputs agree to bf16 precision, so only candidates whose probabilities lie
+    # within a few per cent of each other can swap
+    for t in np.nonzero(~same_path)[0]:
+        l = next(l for l in range(cfg.n_layers) if np.any(got_ids[l][t] != results[l]["tok_ids"][t]))
+        if any(shortlist_diffs[:l + 1]):
+            continue
+        g = results[l]["probs"][t]
+        swapped = set(got_ids[l][t].tolist()) ^ set(results[l]["tok_ids"][t].tolist())
+        vals = [g[e] for e in swapped if e >= 0]
+        if len(vals) >= 2:
+            assert (max(vals) - min(vals)) / max(vals) < 0.15, (int(t), l, vals)
+    # eight layers of bf16 storage: each adds up to half an ulp of the running state (2^-9 relative) on top of the
+    # per-layer MoE tolerance
+    assert err_same <= cfg.n_layers * (2e-2 + 2.0 ** -9 * scale), (err_same, scale)
+    assert err_same / scale <= 2e-2
+
+
+class _LazyF64:
+    """Per-expert fp64 view of a stacked bf16 weight tensor, widened on first use (memory only, no arithmetic)."""
+
+    def __init__(self, stacked):
+        self._w, self._cache = stacked, {}
+
+    def __getitem__(self, e):
+        if e not in self._cache:
+            self._cache[e] = wl.as_f32(self._w[e]).astype(np.float64)
+        return self._cache[e]
