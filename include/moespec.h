@@ -179,7 +179,6 @@ moespec_status moespec_expert_ffn(const moespec_desc *desc, const moespec_weight
  * taps is given: without them the expert passes find their segments themselves.  The output is the
  * same, bit for bit, either way.
  */
-#define MOESPEC_TRACE_POINTS 6
 typedef struct {
   double  *probs;
   double  *scores;
@@ -190,11 +189,6 @@ typedef struct {
   int32_t *seg_off;
   int32_t *perm;
   int32_t *n_loaded;
-  /* Optional timing hook for benchmarks (HOST array, or NULL): MOESPEC_TRACE_POINTS hipEvent_t handles,
-   * created by the caller with timing enabled.  They are recorded on the stream at the stage
-   * boundaries: [0] start, [1] after routing, [2] after budget + segments, [3] after the gate/up
-   * pass, [4] after the down pass, [5] after the combine. */
-  void *const *trace_events;
 } moespec_taps;
 
 moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_weights *weights,
@@ -203,6 +197,23 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
                                      const void *residual, void *out,
                                      const moespec_taps *taps,
                                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Measurement aid, not part of the method: moespec_layer_forward (no taps) that also records HIP events on the
+ * stream at its stage boundaries, so that a benchmark can time the stages of one call without a profiler.
+ *   trace_events  HOST array of MOESPEC_TRACE_POINTS hipEvent_t handles created by the caller with timing
+ *                 enabled (entries may be NULL): [0] start, [1] after the prologue (router, scores, shortlist,
+ *                 restricted routing, pair grouping), [2] after the gate/up pass, [3] after the down pass,
+ *                 [4] after the combine.
+ * An event interval brackets the launches in it and includes their dispatch latency.
+ */
+#define MOESPEC_TRACE_POINTS 5
+moespec_status moespec_layer_forward_traced(const moespec_desc *desc, const moespec_weights *weights,
+                                            const void *h, int32_t M, int32_t B, int32_t policy,
+                                            const int32_t *ext_shortlist,
+                                            const void *residual, void *out, int32_t *n_loaded,
+                                            void *const *trace_events,
+                                            void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * moespec_layer_forward for callers that cannot allocate device memory or pass a workspace: code under HIP

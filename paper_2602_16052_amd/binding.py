@@ -25,7 +25,7 @@ GATE_SOFTMAX, GATE_SIGMOID = 0, 1
 
 EXPORTS = ("moespec_abi_version", "moespec_status_string", "moespec_check_desc", "moespec_workspace_bytes",
            "moespec_route", "moespec_budget", "moespec_expert_ffn", "moespec_layer_forward",
-           "moespec_layer_forward_static", "moespec_stack_forward", "moespec_rms_scale",
+           "moespec_layer_forward_traced", "moespec_layer_forward_static", "moespec_stack_forward", "moespec_rms_scale",
            "moespec_calibration_count", "moespec_static_shortlist", "moespec_coverage_curve",
            "moespec_reconstruction_error", "moespec_oracle_ranking", "moespec_stream_read")
 
@@ -49,11 +49,11 @@ class Weights(Structure):
 class Taps(Structure):
     _fields_ = [("probs", c_void_p), ("scores", c_void_p), ("budget_ids", c_void_p), ("tok_ids", c_void_p),
                 ("tok_w", c_void_p), ("seg_expert", c_void_p), ("seg_off", c_void_p), ("perm", c_void_p),
-                ("n_loaded", c_void_p), ("trace_events", POINTER(c_void_p))]
+                ("n_loaded", c_void_p)]
 
 
-TRACE_POINTS = 6
-TRACE_STAGES = ("route", "budget", "gate_up", "down", "combine")   # intervals between consecutive trace points
+TRACE_POINTS = 5
+TRACE_STAGES = ("prologue", "gate_up", "down", "combine")   # intervals between consecutive trace points
 
 
 _lib = None
@@ -91,6 +91,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moespec_layer_forward.restype = c_int32
     lib.moespec_layer_forward.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_int32,
                                           c_void_p, c_void_p, c_void_p, POINTER(Taps), c_void_p, c_size_t, c_void_p]
+    lib.moespec_layer_forward_traced.restype = c_int32
+    lib.moespec_layer_forward_traced.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_int32,
+                                                 c_void_p, c_void_p, c_void_p, c_void_p, POINTER(c_void_p), c_void_p,
+                                                 c_size_t, c_void_p]
     lib.moespec_layer_forward_static.restype = c_int32
     lib.moespec_layer_forward_static.argtypes = [POINTER(Desc), POINTER(Weights), c_void_p, c_int32, c_int32, c_int32,
                                                  c_void_p, c_void_p, c_void_p, c_void_p]
@@ -297,7 +301,8 @@ class HipEvents:
 
 class LayerForwardCall:
     """moespec_layer_forward with its arguments marshalled once: calling the object only crosses the
-    C ABI (for tight loops, where per-call marshalling would cost more than the kernels)."""
+    C ABI (for tight loops, where per-call marshalling would cost more than the kernels).  With ``trace`` the call
+    goes through moespec_layer_forward_traced, which records the events at the stage boundaries."""
 
     def __init__(self, desc: LayerDesc, weights: Dict[str, torch.Tensor], h: torch.Tensor, B: int, policy: int,
                  ws: torch.Tensor, out: torch.Tensor, ext_shortlist: Optional[torch.Tensor] = None,
@@ -305,27 +310,30 @@ class LayerForwardCall:
                  n_loaded: Optional[torch.Tensor] = None, stream=None):
         M, dt = h.shape[0], desc.torch_dtype
         self._keep = (weights, h, ws, out, ext_shortlist, residual, trace, n_loaded)
-        self._fn = load_library().moespec_layer_forward
+        lib = load_library()
         self._cd, self._cw = desc.c(), _weights(desc, weights, True, True)
-        self._taps = None
-        if trace is not None or n_loaded is not None:
-            self._taps = Taps()
-            if trace is not None:
-                if len(trace.handles) < TRACE_POINTS:
-                    raise ValueError(f"trace needs {TRACE_POINTS} events")
-                self._taps.trace_events = ctypes.cast(trace.handles, POINTER(c_void_p))
+        head = (ctypes.byref(self._cd), ctypes.byref(self._cw), _ptr(h, dt, M * desc.d, "h"), M, int(B),
+                int(policy), _ptr(ext_shortlist, torch.int32, max(int(B), 0), "ext_shortlist"),
+                _ptr(residual, dt, M * desc.d, "residual"), _ptr(out, dt, M * desc.d, "out"))
+        tail = (_ptr(ws), ws.numel(), _stream(stream))
+        if trace is not None:
+            if len(trace.handles) < TRACE_POINTS:
+                raise ValueError(f"trace needs {TRACE_POINTS} events")
+            self._fn, self._name = lib.moespec_layer_forward_traced, "moespec_layer_forward_traced"
+            self._args = head + (_ptr(n_loaded, torch.int32, 1, "n_loaded"),
+                                 ctypes.cast(trace.handles, POINTER(c_void_p))) + tail
+        else:
+            self._fn, self._name = lib.moespec_layer_forward, "moespec_layer_forward"
+            self._taps = None
             if n_loaded is not None:
+                self._taps = Taps()
                 self._taps.n_loaded = _ptr(n_loaded, torch.int32, 1, "n_loaded")
-        self._args = (ctypes.byref(self._cd), ctypes.byref(self._cw), _ptr(h, dt, M * desc.d, "h"), M, int(B),
-                      int(policy), _ptr(ext_shortlist, torch.int32, max(int(B), 0), "ext_shortlist"),
-                      _ptr(residual, dt, M * desc.d, "residual"), _ptr(out, dt, M * desc.d, "out"),
-                      ctypes.byref(self._taps) if self._taps is not None else None, _ptr(ws), ws.numel(),
-                      _stream(stream))
+            self._args = head + (ctypes.byref(self._taps) if self._taps is not None else None,) + tail
 
     def __call__(self):
         st = self._fn(*self._args)
         if st != OK:
-            raise MoeSpecError(int(st), "moespec_layer_forward")
+            raise MoeSpecError(int(st), self._name)
 
 
 def moespec_layer_forward(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: torch.Tensor, B: int, policy: int,
@@ -347,7 +355,7 @@ def moespec_layer_forward(desc: LayerDesc, weights: Dict[str, torch.Tensor], h: 
                      tok_ids=torch.empty((M, k), **i32), tok_w=torch.empty((M, k), dtype=torch.float32, device=dev),
                      seg_expert=torch.empty(nb, **i32), seg_off=torch.empty(nb + 1, **i32),
                      perm=torch.empty(M * k, **i32), n_loaded=torch.empty(1, **i32))
-        ctaps = Taps(**{key: _ptr(val) for key, val in tap_t.items()})   # trace_events stays NULL
+        ctaps = Taps(**{key: _ptr(val) for key, val in tap_t.items()})
     cd, cw = desc.c(), _weights(desc, weights, True, True)
     st = load_library().moespec_layer_forward(
         ctypes.byref(cd), ctypes.byref(cw), _ptr(h, dt, M * desc.d, "h"), M, int(B), int(policy),

@@ -94,7 +94,7 @@ moespec_status check_layer_args(const moespec_desc *desc, const moespec_weights 
 moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *weights, const void *h,
                                      int32_t M, int32_t B, int32_t policy, const int32_t *ext_shortlist,
                                      const void *residual, void *out, const moespec_taps *taps, void *ws,
-                                     size_t ws_bytes, void *hip_stream) {
+                                     size_t ws_bytes, void *hip_stream, void *const *tr = nullptr) {
   moespec_status s = check_common(desc, M, ws, ws_bytes);
   if (s != MOESPEC_OK) return s;
   if ((s = check_layer_args(desc, weights, h, B, policy, residual, out)) != MOESPEC_OK) return s;
@@ -109,7 +109,6 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
   int32_t *seg_off = t.seg_off ? t.seg_off : w.seg_off;
   int32_t *perm = t.perm ? t.perm : w.perm;
   int32_t *budget_ids = t.budget_ids ? t.budget_ids : w.budget_ids;
-  void *const *tr = t.trace_events;
   auto mark = [&](int i) {
     if (tr && tr[i]) (void)hipEventRecord(static_cast<hipEvent_t>(tr[i]), st);
   };
@@ -122,9 +121,8 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
                                          t.seg_off, t.perm, t.n_loaded, st);
     if (e != hipSuccess) return MOESPEC_ERR_HIP;
     mark(1);
-    mark(2);
     e = launch_expert_ffn(*desc, *weights, h, M, B, nullptr, nullptr, nullptr, tok_ids, tok_w, residual, out, w.act,
-                          w.y, w.items, false, w.list_count, budget_ids, nullptr, nullptr, st, tr ? tr + 3 : nullptr,
+                          w.y, w.items, false, w.list_count, budget_ids, nullptr, nullptr, st, tr ? tr + 2 : nullptr,
                           w.lists, M);
     return from_hip(e);
   }
@@ -134,14 +132,13 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
   const bool want_segments = !self_seg || t.seg_off || t.perm || t.n_loaded;
   hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, w.done, 1 + desc->n_experts, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
-  mark(1);
   e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, budget_ids, tok_ids, tok_w, seg_expert,
                     seg_off, perm, t.n_loaded, w.items, w.done, true, want_segments, w.scores, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
-  mark(2);
+  mark(1);
   e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
                         w.y, w.items, want_segments, self_seg ? w.done + 1 : nullptr, budget_ids, w.pub_items,
-                        w.pub_lists, st, tr ? tr + 3 : nullptr);
+                        w.pub_lists, st, tr ? tr + 2 : nullptr);
   return from_hip(e);
 }
 
@@ -149,7 +146,7 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
 
 extern "C" {
 
-int32_t moespec_abi_version(void) { return 4; }
+int32_t moespec_abi_version(void) { return 5; }
 
 const char *moespec_status_string(int32_t status) {
   switch (status) {
@@ -216,6 +213,16 @@ moespec_status moespec_layer_forward(const moespec_desc *desc, const moespec_wei
                                      const void *residual, void *out, const moespec_taps *taps, void *ws,
                                      size_t ws_bytes, void *hip_stream) {
   return layer_forward(desc, weights, h, M, B, policy, ext_shortlist, residual, out, taps, ws, ws_bytes, hip_stream);
+}
+
+moespec_status moespec_layer_forward_traced(const moespec_desc *desc, const moespec_weights *weights, const void *h,
+                                            int32_t M, int32_t B, int32_t policy, const int32_t *ext_shortlist,
+                                            const void *residual, void *out, int32_t *n_loaded,
+                                            void *const *trace_events, void *ws, size_t ws_bytes, void *hip_stream) {
+  moespec_taps t{};
+  t.n_loaded = n_loaded;
+  return layer_forward(desc, weights, h, M, B, policy, ext_shortlist, residual, out, &t, ws, ws_bytes, hip_stream,
+                       trace_events);
 }
 
 moespec_status moespec_layer_forward_static(const moespec_desc *desc, const moespec_weights *weights, const void *h,

@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert mb.abi_version() == 4
+    assert mb.abi_version() == 5
     assert mb.status_string(mb.OK) == "ok"
     assert "workspace" in mb.status_string(mb.ERR_WORKSPACE_TOO_SMALL)
     assert mb.status_string(99) == "unknown status"

@@ -78,3 +78,21 @@ def test_router_bias_gives_heavy_tailed_routing(name):
     m = O.decision_margins(g, 32, cfg.top_k, O.shortlist(s, 32))
     # fp64 decisions: any gap far above 1e-12 cannot be flipped by summation order or exp rounding
     assert min(m.values()) > 1e-9, m
+
+
+def test_stored_stack_scales_show_why_the_stack_scales_its_layer_inputs(golden_dir):
+    """tests/golden/coarse_stack_literal_scales.json (written by make_stack_literal_scales.py from the oracle alone):
+    under the recurrence as the workload words it the hidden scale squares from layer to layer, the router saturates
+    to one-hot probabilities and the state leaves the bf16 range before the 8 layers are through; with unit-RMS layer
+    inputs the MoE outputs stay at one scale."""
+    import json
+    import os
+    data = json.load(open(os.path.join(golden_dir, "coarse_stack_literal_scales.json")))
+    lit, pre = data["literal"], data["pre_norm"]
+    rms = [r["input_rms"] for r in lit]
+    assert all(b > 4.0 * a for a, b in zip(rms[1:], rms[2:])), rms            # faster than geometric growth
+    assert rms[4] > 1e5 and any(r["max_routing_prob"] == 1.0 for r in lit)     # softmax saturated
+    assert not lit[-1]["next_state_finite_in_bf16"] and len(lit) < 8           # overflow before the last layer
+    assert len(pre) == 8 and all(r["next_state_finite_in_bf16"] for r in pre)
+    outs = [r["moe_output_max_abs"] for r in pre]
+    assert max(outs) / min(outs) < 1.5, outs
