@@ -258,37 +258,25 @@ __global__ __launch_bounds__(kPrologueThreads) void route_budget_kernel(
   if (probs_out)
     for (int i = tid; i < N; i += nt) probs_out[(size_t)own * N + i] = g[own * NS + i];
 
-  // Eq. (5): s_i = sum_t g_i(h_t).  Column i is cut into `parts` runs of tokens that are summed side by side and
-  // then added in run order.
+  // Eq. (5): s_i = sum_t g_i(h_t).  16 lanes share a column: lane p adds tokens p, p + 16, ... in ascending order
+  // and the 16 partial sums are folded through DPP; 64 columns per round.
   int np2 = 1, np2_log = 0;
   while (np2 < N) np2 <<= 1, ++np2_log;
   const int parts = nt >> np2_log;  // N <= 256: at least 4
   const int ci = tid & (np2 - 1), cp = tid >> np2_log;
   if (ext_shortlist == nullptr || scores_out != nullptr) {
-    const int per = (M + parts - 1) / parts;
-    double a = 0.0;
-    if (ci < N) {
-      const int t1 = min(M, (cp + 1) * per);
-      for (int t = cp * per; t < t1; t += 4) {  // fixed blocks of 4: the loads go out together
+    for (int c0 = 0; c0 < N; c0 += nt / 16) {
+      const int col = min(c0 + (tid >> 4), N - 1);
+      double a = 0.0;
+      for (int t = seg; t < M; t += 64) {  // fixed blocks of 4 tokens: the loads go out together
         double v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = t + u < t1 ? g[(t + u) * NS + ci] : 0.0;
+        for (int u = 0; u < 4; ++u) v[u] = t + 16 * u < M ? g[(t + 16 * u) * NS + col] : 0.0;
 #pragma unroll
         for (int u = 0; u < 4; ++u) a += v[u];  // rows past the end add +0.0, which leaves the sum unchanged
       }
-    }
-    red[cp * np2 + ci] = a;
-    __syncthreads();
-    if (tid < N) {
-      double acc = 0.0;
-      for (int p = 0; p < parts; p += 4) {  // parts is a multiple of 4
-        double v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = red[(p + u) * np2 + tid];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) acc += v[u];
-      }
-      s[tid] = acc;
+      a = row16_sum(a);
+      if (seg == 0 && c0 + (tid >> 4) < N) s[col] = a;
     }
     __syncthreads();
   }
@@ -373,6 +361,7 @@ __global__ __launch_bounds__(kPrologueThreads) void route_budget_kernel(
   // unchanged; Eq. (8) takes the top-k inside S and weights over that selection.  A candidate's rank is the number
   // of candidates that go before it; rank r < k fills slot r.  Thread (x, p): candidate x against the p-th share
   // of the rivals.
+  int cand_j = -1;
   {
     const double *grow = g + own * NS;
     int cp2 = 64, cp2_log = 6;  // candidates rounded up to a power of two, at least one wave
@@ -394,10 +383,16 @@ __global__ __launch_bounds__(kPrologueThreads) void route_budget_kernel(
       for (int u = 0; u < 4; ++u) c += (int)((y + u < y1) & (jy[u] >= 0) & before(vy[u], jy[u], v, j));
     }
     if (c && j >= 0) atomicAdd(&rank[x], c);  // rank[] is zero again here; j >= 0 implies x < n_cand <= N
-    __syncthreads();
-    if (tid < n_cand && j >= 0 && rank[tid] < k) sel[rank[tid]] = j;
-    __syncthreads();
+    cand_j = j;
+  }
+  // the two remaining steps of the token's routing wait for one barrier each; they ride on the barriers of the first
+  // pair-list round below when this workgroup has one
+  auto token_fill_slots = [&]() {
+    if (tid < n_cand && cand_j >= 0 && rank[tid] < k) sel[rank[tid]] = cand_j;
+  };
+  auto token_write = [&]() {
     if (tid < k) {
+      const double *grow = g + own * NS;
       double denom = 0.0;  // over the selected set in slot order (before any slot is dropped: Eq. (7))
       for (int sl = 0; sl < k; ++sl) {
         const int e = sel[sl];
@@ -409,7 +404,8 @@ __global__ __launch_bounds__(kPrologueThreads) void route_budget_kernel(
       tok_ids[(size_t)own * k + tid] = keep ? e : -1;
       tok_w[(size_t)own * k + tid] = (float)w;
     }
-  }
+  };
+  bool token_done = false;
 
   // Pair lists of the shortlist ranks own, own + M, ...: token t is routed to expert e = S[r] iff e ranks among the
   // first k of t's candidates; its rank is the slot.  16 lanes share a token and split its rivals; 64 tokens per
@@ -436,9 +432,12 @@ __global__ __launch_bounds__(kPrologueThreads) void route_budget_kernel(
       c = row16_sum(c);
       const bool routed = real & (t0 + (tid >> 4) < M) & (seg == 0) & (c < k) & (ge == ge);  // NaN ranks nowhere
       const unsigned long long mask = __ballot(routed);
-      __syncthreads();  // the wave counts of the previous round have been read
+      __syncthreads();  // the wave counts of the previous round have been read (and the rank counts are complete)
+      if (!token_done) token_fill_slots();
       if (lane == 0) red[wave] = (double)__popcll(mask);
       __syncthreads();
+      if (!token_done) token_write();
+      token_done = true;
       int at = base, total = 0;
 #pragma unroll
       for (int w = 0; w < nt / kWave; ++w) {
@@ -451,6 +450,12 @@ __global__ __launch_bounds__(kPrologueThreads) void route_budget_kernel(
       base += total;
     }
     if (tid == 0) list_count[r] = base;
+  }
+  if (!token_done) {  // a workgroup without a pair list
+    __syncthreads();
+    token_fill_slots();
+    __syncthreads();
+    token_write();
   }
 }
 
