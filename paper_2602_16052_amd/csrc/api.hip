@@ -116,7 +116,8 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
   if (fused_prologue_ok(*desc, M) && expert_ffn_self_segmenting(*desc, M)) {
     // Small trees: two launches leave the shortlist, the restricted routing and every loaded expert's pair
     // list; the expert passes pick their work items from those lists.
-    hipError_t e = launch_fused_prologue(*desc, *weights, h, M, B, policy, ext_shortlist, w.partial, t.probs, t.scores,
+    hipError_t e = launch_fused_prologue(*desc, *weights, h, M, B, policy, ext_shortlist, w.partial, w.probs, t.probs,
+                                         t.scores,
                                          budget_ids, t.seg_expert, tok_ids, tok_w, w.list_count, w.lists, M,
                                          t.seg_off, t.perm, t.n_loaded, st);
     if (e != hipSuccess) return MOESPEC_ERR_HIP;

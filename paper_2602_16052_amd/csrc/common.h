@@ -228,7 +228,8 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
 bool fused_prologue_ok(const moespec_desc &ds, int M);
 int logit_slices(const moespec_desc &ds, int M);
 hipError_t launch_fused_prologue(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int B,
-                                 int policy, const int32_t *ext_shortlist, double *partial, double *probs_out,
+                                 int policy, const int32_t *ext_shortlist, double *partial, double *probs_ws,
+                                 double *probs_out,
                                  double *scores_out, int32_t *budget_ids, int32_t *seg_expert, int32_t *tok_ids,
                                  float *tok_w, int32_t *list_count, int32_t *lists, int list_stride,
                                  int32_t *seg_off, int32_t *perm, int32_t *n_loaded, hipStream_t st);
