@@ -131,7 +131,9 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
   // the pairs only if the caller asked for the segment arrays or the passes need them.
   const bool self_seg = expert_ffn_self_segmenting(*desc, M);
   const bool want_segments = !self_seg || t.seg_off || t.perm || t.n_loaded;
-  hipError_t e = launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, w.done, 1 + desc->n_experts, st);
+  hipError_t e = mfma_route_ok(*desc, M)
+                     ? launch_mfma_route(*desc, *weights, h, M, w.partial, probs, w.done, 1 + desc->n_experts, st)
+                     : launch_route(*desc, *weights, h, M, probs, nullptr, nullptr, w.done, 1 + desc->n_experts, st);
   if (e != hipSuccess) return MOESPEC_ERR_HIP;
   e = launch_budget(*desc, probs, M, B, policy, ext_shortlist, t.scores, budget_ids, tok_ids, tok_w, seg_expert,
                     seg_off, perm, t.n_loaded, w.items, w.done, true, want_segments, w.scores, st);

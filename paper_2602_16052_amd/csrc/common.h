@@ -226,6 +226,11 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
 // ascending).  partial: [logit_slices, M, N] doubles of scratch.  probs_out, scores_out, seg_expert, seg_off,
 // perm, n_loaded are optional copies for the caller (the last three cost one more small launch).
 bool fused_prologue_ok(const moespec_desc &ds, int M);
+// Stage 1 on the matrix cores for bf16 layers of up to kSelfMaxExperts experts and kSelfMaxTokens tokens, whatever the
+// size of the table: probs [M, N] out, partial as above, zero_words cleared like launch_route does.
+bool mfma_route_ok(const moespec_desc &ds, int M);
+hipError_t launch_mfma_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *partial,
+                             double *probs, int32_t *zero_words, int n_zero, hipStream_t st);
 int logit_slices(const moespec_desc &ds, int M);
 hipError_t launch_fused_prologue(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int B,
                                  int policy, const int32_t *ext_shortlist, double *partial, double *probs_ws,

@@ -143,8 +143,11 @@ __device__ __forceinline__ double exp_nonpos(double x) {
 template <int Q>
 __global__ __launch_bounds__(kWave) void softmax_rows_kernel(const double *__restrict__ partial,
                                                             const float *__restrict__ bias, int M, int N,
-                                                            int sigmoid_gate, double *__restrict__ probs) {
+                                                            int sigmoid_gate, double *__restrict__ probs,
+                                                            int32_t *__restrict__ zero_words, int n_zero) {
   const int t = blockIdx.x, lane = threadIdx.x;
+  if (zero_words && t == 0)  // counters of a later kernel, cleared here instead of by a launch of their own
+    for (int i = lane; i < n_zero; i += kWave) zero_words[i] = 0;
   const size_t MN = (size_t)M * N;
   double val[4];
 #pragma unroll
@@ -591,6 +594,29 @@ int logit_slices(const moespec_desc &ds, int M) {
   return best;
 }
 
+// Stage 1 alone for bf16 layers whose table does not fit the fused kernel's LDS: matrix-core projection, then the
+// row-wise gate; also clears n_zero counters for the staged budget kernel.
+bool mfma_route_ok(const moespec_desc &ds, int M) {
+  return ds.dtype == MOESPEC_BF16 && ds.n_experts <= kSelfMaxExperts && M <= kSelfMaxTokens;
+}
+hipError_t launch_mfma_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *partial,
+                             double *probs, int32_t *zero_words, int n_zero, hipStream_t st) {
+  const int N = ds.n_experts, q = logit_slices(ds, M), sig = ds.gate == MOESPEC_GATE_SIGMOID ? 1 : 0;
+  dim3 grid(((M + 15) / 16) * ((N + 15) / 16), q);
+  logits_mfma_kernel<<<grid, kLogitWaves * kWave, 0, st>>>(static_cast<const uint16_t *>(h),
+                                                          static_cast<const uint16_t *>(wt.w_router), M, N, ds.d, q,
+                                                          partial);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  switch (q) {
+    case 1: softmax_rows_kernel<1><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs, zero_words, n_zero); break;
+    case 2: softmax_rows_kernel<2><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs, zero_words, n_zero); break;
+    case 4: softmax_rows_kernel<4><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs, zero_words, n_zero); break;
+    default: softmax_rows_kernel<8><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs, zero_words, n_zero); break;
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_fused_prologue(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int B,
                                  int policy, const int32_t *ext_shortlist, double *partial, double *probs_ws,
                                  double *probs_out,
@@ -616,10 +642,10 @@ hipError_t launch_fused_prologue(const moespec_desc &ds, const moespec_weights &
   if (split) {
     double *probs = probs_out ? probs_out : probs_ws;
     switch (q) {
-      case 1: softmax_rows_kernel<1><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs); break;
-      case 2: softmax_rows_kernel<2><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs); break;
-      case 4: softmax_rows_kernel<4><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs); break;
-      default: softmax_rows_kernel<8><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs); break;
+      case 1: softmax_rows_kernel<1><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs, nullptr, 0); break;
+      case 2: softmax_rows_kernel<2><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs, nullptr, 0); break;
+      case 4: softmax_rows_kernel<4><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs, nullptr, 0); break;
+      default: softmax_rows_kernel<8><<<M, kWave, 0, st>>>(partial, wt.b_router, M, N, sig, probs, nullptr, 0); break;
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     table = probs;
