@@ -94,7 +94,8 @@ moespec_status check_layer_args(const moespec_desc *desc, const moespec_weights 
 moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *weights, const void *h,
                                      int32_t M, int32_t B, int32_t policy, const int32_t *ext_shortlist,
                                      const void *residual, void *out, const moespec_taps *taps, void *ws,
-                                     size_t ws_bytes, void *hip_stream, void *const *tr = nullptr) {
+                                     size_t ws_bytes, void *hip_stream, void *const *tr = nullptr,
+                                     void *x_next = nullptr) {
   moespec_status s = check_common(desc, M, ws, ws_bytes);
   if (s != MOESPEC_OK) return s;
   if ((s = check_layer_args(desc, weights, h, B, policy, residual, out)) != MOESPEC_OK) return s;
@@ -124,7 +125,7 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
     mark(1);
     e = launch_expert_ffn(*desc, *weights, h, M, B, nullptr, nullptr, nullptr, tok_ids, tok_w, residual, out, w.act,
                           w.y, w.items, false, w.list_count, budget_ids, nullptr, nullptr, st, tr ? tr + 2 : nullptr,
-                          w.lists, M);
+                          w.lists, M, x_next);
     return from_hip(e);
   }
   // Other shapes: the expert passes derive their segments themselves where they can, and the budget stage groups
@@ -141,7 +142,7 @@ moespec_status layer_forward(const moespec_desc *desc, const moespec_weights *we
   mark(1);
   e = launch_expert_ffn(*desc, *weights, h, M, B, seg_expert, seg_off, perm, tok_ids, tok_w, residual, out, w.act,
                         w.y, w.items, want_segments, self_seg ? w.done + 1 : nullptr, budget_ids, w.pub_items,
-                        w.pub_lists, st, tr ? tr + 2 : nullptr);
+                        w.pub_lists, st, tr ? tr + 2 : nullptr, nullptr, 0, x_next);
   return from_hip(e);
 }
 
@@ -265,7 +266,8 @@ moespec_status moespec_stack_forward(const moespec_desc *desc, const moespec_wei
   for (int32_t l = 0; l < n_layers; ++l) {
     const void *x = h;
     if (pre_norm) {
-      if (launch_rms_scale(*desc, h, M, w.xnorm, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+      // the first layer's input is scaled by a launch of its own; every later one by the combine of the layer before
+      if (l == 0 && launch_rms_scale(*desc, h, M, w.xnorm, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return MOESPEC_ERR_HIP;
       x = w.xnorm;
     }
@@ -273,8 +275,10 @@ moespec_status moespec_stack_forward(const moespec_desc *desc, const moespec_wei
     t.budget_ids = budget_ids ? budget_ids + (size_t)l * B : nullptr;
     t.tok_ids = tok_ids ? tok_ids + (size_t)l * M * desc->top_k : nullptr;
     // the combine reads residual[t, j] and writes out[t, j] in the same thread, after every kernel that reads the
-    // layer input: updating the residual stream in place is safe
-    if ((s = layer_forward(desc, &layers[l], x, M, B, policy, nullptr, h, h, &t, ws, ws_bytes, hip_stream)) != MOESPEC_OK)
+    // layer input: updating the residual stream (and, for the next layer, the scaled input) in place is safe
+    void *x_next = (pre_norm && l + 1 < n_layers) ? w.xnorm : nullptr;
+    if ((s = layer_forward(desc, &layers[l], x, M, B, policy, nullptr, h, h, &t, ws, ws_bytes, hip_stream, nullptr,
+                           x_next)) != MOESPEC_OK)
       return s;
   }
   return MOESPEC_OK;

@@ -29,10 +29,12 @@ template <typename T> struct Elem;
 template <> struct Elem<float> {
   static __device__ __forceinline__ float load(const float *p) { return *p; }
   static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+  static __device__ __forceinline__ float stored(float v) { return v; }  // the value a store of v leaves behind
 };
 template <> struct Elem<uint16_t> {
   static __device__ __forceinline__ float load(const uint16_t *p) { return bf16_bits_to_float(*p); }
   static __device__ __forceinline__ void store(uint16_t *p, float v) { *p = float_to_bf16_bits(v); }
+  static __device__ __forceinline__ float stored(float v) { return bf16_bits_to_float(float_to_bf16_bits(v)); }
 };
 
 // Ranking order used by every selection: larger value first, then lower index.
@@ -54,6 +56,27 @@ __device__ __forceinline__ double wave_max(double v) {
 #pragma unroll
   for (int s = 32; s >= 1; s >>= 1) v = fmax(v, __shfl_xor(v, s, kWave));
   return v;
+}
+
+// x = row / sqrt(mean of squares) in fp32 for one row held by a workgroup of kRmsThreads threads: thread i holds the
+// elements (c * kRmsThreads + i) * 4 .. + 3 of chunk c = 0 .. 7 in v[c][0..3] (zeros past the row end).  Squares are
+// added chunk by chunk and element by element per thread, the per-thread sums pairwise through LDS (a fixed tree):
+// the result depends on the values alone.  Used by rms_scale_kernel and by the combine that also writes the next
+// layer's input, which therefore agree bit for bit.  part: kRmsThreads floats of LDS.  Synchronises.
+constexpr int kRmsThreads = 256;
+__device__ inline float rms_scale_of_row(const float (&v)[8][4], int d, float *part) {
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ss = fmaf(v[c][i], v[c][i], ss);
+  part[threadIdx.x] = ss;
+  __syncthreads();
+  for (int s = kRmsThreads / 2; s >= 1; s >>= 1) {
+    if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+    __syncthreads();
+  }
+  return 1.0f / sqrtf(part[0] / (float)d);
 }
 
 // Rank-count selection of the k best of v[0..n) restricted to candidates with member[i] != 0
@@ -214,12 +237,15 @@ hipError_t launch_budget(const moespec_desc &ds, const double *probs, int M, int
 // which the gate/up pass of that mode leaves its work items for the down pass (NULL: the down pass derives
 // them again).
 // trace (may be NULL): 3 events recorded after the gate/up pass, the down pass and the combine.
+// x_next (may be NULL): [M, d] dtype; the combine then also writes out scaled row by row to unit root-mean-square,
+// the next layer's input in a stack (d <= 8192).
 hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int n_seg,
                              const int32_t *seg_expert, const int32_t *seg_off, const int32_t *perm,
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
                              float *y, int4 *items, bool items_ready, const int32_t *rank_count,
                              const int32_t *shortlist, int4 *pub_items, int32_t *pub_lists, hipStream_t st,
-                             void *const *trace = nullptr, const int32_t *lists = nullptr, int list_stride = 0);
+                             void *const *trace = nullptr, const int32_t *lists = nullptr, int list_stride = 0,
+                             void *x_next = nullptr);
 // The fused prologue of the layer call (prologue.hip): router projection on the fp64 matrix cores, then one
 // launch that leaves the shortlist (budget_ids), the restricted routing (tok_ids, tok_w) and, for every shortlist
 // rank r, the pairs routed to its expert (list_count[r]; lists[r * list_stride ..], flat ids t * k + slot, tokens

@@ -724,15 +724,12 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_down_f32_kernel(
 // Four consecutive outputs per thread; y holds `splits` partial copies split_stride floats apart (K-split
 // down pass).  The rows of dropped slots hold stale scratch: they are loaded
 // (valid memory) but never enter the sum.
+// the four outputs j .. j+3 of token t (before storage rounding)
 template <typename T>
-__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ y, const int32_t *__restrict__ tok_ids,
-                                                      const float *__restrict__ tok_w, const T *__restrict__ residual,
-                                                      int k, int d, int splits, size_t split_stride,
-                                                      T *__restrict__ out) {
-  const int t = blockIdx.y;
-  const int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (j >= d) return;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+__device__ __forceinline__ f32x4 combine_four(const float *__restrict__ y, const int32_t *__restrict__ tok_ids,
+                                              const float *__restrict__ tok_w, const T *__restrict__ residual, int t,
+                                              int j, int k, int d, int splits, size_t split_stride) {
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   if (residual) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = Elem<T>::load(residual + (size_t)t * d + j + i);
@@ -768,8 +765,59 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
       for (int i = 0; i < 4; ++i) acc[i] = fmaf(w, v[i], acc[i]);
     }
   }
+  return acc;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ y, const int32_t *__restrict__ tok_ids,
+                                                      const float *__restrict__ tok_w, const T *__restrict__ residual,
+                                                      int k, int d, int splits, size_t split_stride,
+                                                      T *__restrict__ out) {
+  const int t = blockIdx.y;
+  const int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (j >= d) return;
+  const f32x4 acc = combine_four<T>(y, tok_ids, tok_w, residual, t, j, k, d, splits, split_stride);
 #pragma unroll
   for (int i = 0; i < 4; ++i) Elem<T>::store(out + (size_t)t * d + j + i, acc[i]);
+}
+
+// The combine of a layer inside a stack that scales its layer inputs: one workgroup per token writes the row of the
+// new hidden state and, from the STORED (rounded) values, the next layer's input x = row / rms(row) - with the
+// element-to-thread mapping and summation order of rms_scale_row, so that the result equals, bit for bit, what
+// rms_scale_kernel makes of the stored row.  d <= 8192: a thread holds up to 32 outputs.
+template <typename T>
+__global__ __launch_bounds__(kRmsThreads) void combine_scale_kernel(const float *__restrict__ y,
+                                                                    const int32_t *__restrict__ tok_ids,
+                                                                    const float *__restrict__ tok_w,
+                                                                    const T *__restrict__ residual, int k, int d,
+                                                                    int splits, size_t split_stride,
+                                                                    T *__restrict__ out, T *__restrict__ x_next) {
+  __shared__ float part[kRmsThreads];
+  const int t = blockIdx.x, tid = threadIdx.x;
+  float v[8][4];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int j = (c * kRmsThreads + tid) * 4;
+    if (j < d) {
+      const f32x4 acc = combine_four<T>(y, tok_ids, tok_w, residual, t, j, k, d, splits, split_stride);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        Elem<T>::store(out + (size_t)t * d + j + i, acc[i]);
+        v[c][i] = Elem<T>::stored(acc[i]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[c][i] = 0.f;
+    }
+  }
+  const float scale = rms_scale_of_row(v, d, part);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int j = (c * kRmsThreads + tid) * 4;
+    if (j < d)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Elem<T>::store(x_next + (size_t)t * d + j + i, v[c][i] * scale);
+  }
 }
 
 template <int U>
@@ -820,7 +868,7 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
                              const int32_t *tok_ids, const float *tok_w, const void *residual, void *out, void *act,
                              float *y, int4 *items, bool items_ready, const int32_t *rank_count,
                              const int32_t *shortlist, int4 *pub_items, int32_t *pub_lists, hipStream_t st,
-                             void *const *trace, const int32_t *lists, int list_stride) {
+                             void *const *trace, const int32_t *lists, int list_stride, void *x_next) {
   const int d = ds.d, F = ds.d_ff, k = ds.top_k;
   hipError_t e;
   if (lists) pub_items = nullptr;  // every pass reads the prologue's lists: nothing to publish
@@ -869,9 +917,15 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
       mark(pass - 1);
     }
     if (!out) return hipSuccess;  // the caller only wants the per-pair outputs y
-    dim3 cgrid((d / 4 + 255) / 256, M);
-    combine_kernel<uint16_t><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const uint16_t *>(residual), k, d,
-                                                    splits, split_stride, static_cast<uint16_t *>(out));
+    if (x_next) {
+      combine_scale_kernel<uint16_t><<<M, kRmsThreads, 0, st>>>(y, tok_ids, tok_w, static_cast<const uint16_t *>(residual),
+                                                              k, d, splits, split_stride, static_cast<uint16_t *>(out),
+                                                              static_cast<uint16_t *>(x_next));
+    } else {
+      dim3 cgrid((d / 4 + 255) / 256, M);
+      combine_kernel<uint16_t><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const uint16_t *>(residual), k, d,
+                                                      splits, split_stride, static_cast<uint16_t *>(out));
+    }
     e = hipGetLastError();
     mark(2);
     return e;
@@ -890,9 +944,15 @@ hipError_t launch_expert_ffn(const moespec_desc &ds, const moespec_weights &wt, 
   if ((e = hipGetLastError()) != hipSuccess) return e;
   mark(1);
   if (!out) return hipSuccess;
-  dim3 cgrid((d / 4 + 255) / 256, M);
-  combine_kernel<float><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const float *>(residual), k, d, 1,
-                                               split_stride, static_cast<float *>(out));
+  if (x_next) {
+    combine_scale_kernel<float><<<M, kRmsThreads, 0, st>>>(y, tok_ids, tok_w, static_cast<const float *>(residual), k, d,
+                                                         1, split_stride, static_cast<float *>(out),
+                                                         static_cast<float *>(x_next));
+  } else {
+    dim3 cgrid((d / 4 + 255) / 256, M);
+    combine_kernel<float><<<cgrid, 256, 0, st>>>(y, tok_ids, tok_w, static_cast<const float *>(residual), k, d, 1,
+                                                 split_stride, static_cast<float *>(out));
+  }
   e = hipGetLastError();
   mark(2);
   return e;

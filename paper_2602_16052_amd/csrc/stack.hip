@@ -5,29 +5,27 @@
 
 namespace moespec {
 
-constexpr int kRmsThreads = 256;
-
-// x[t] = h[t] / sqrt(mean_j h[t, j]^2) in fp32: thread i adds the squares of elements i, i + 256, ... in ascending
-// order, the 256 partial sums are folded pairwise through LDS (a fixed tree), so the result does not depend on
-// timing.  One workgroup per row; x may alias h (every element is read before the barrier that precedes its store).
+// x[t] = h[t] / sqrt(mean_j h[t, j]^2) in fp32 (rms_scale_of_row: a fixed summation order).  One workgroup per row;
+// x may alias h (every element is read before the barriers that precede its store).  d <= 8192.
 template <typename T>
 __global__ __launch_bounds__(kRmsThreads) void rms_scale_kernel(const T *__restrict__ h, int d, T *x) {
   __shared__ float part[kRmsThreads];
   const int t = blockIdx.x, tid = threadIdx.x;
-  const T *row = h + (size_t)t * d;
-  float ss = 0.f;
-  for (int j = tid; j < d; j += kRmsThreads) {
-    const float v = Elem<T>::load(row + j);
-    ss = fmaf(v, v, ss);
+  float v[8][4];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int j = (c * kRmsThreads + tid) * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[c][i] = j < d ? Elem<T>::load(h + (size_t)t * d + j + i) : 0.f;
   }
-  part[tid] = ss;
-  __syncthreads();
-  for (int s = kRmsThreads / 2; s >= 1; s >>= 1) {
-    if (tid < s) part[tid] += part[tid + s];
-    __syncthreads();
+  const float scale = rms_scale_of_row(v, d, part);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int j = (c * kRmsThreads + tid) * 4;
+    if (j < d)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Elem<T>::store(x + (size_t)t * d + j + i, v[c][i] * scale);
   }
-  const float scale = 1.0f / sqrtf(part[0] / (float)d);
-  for (int j = tid; j < d; j += kRmsThreads) Elem<T>::store(x + (size_t)t * d + j, Elem<T>::load(row + j) * scale);
 }
 
 hipError_t launch_rms_scale(const moespec_desc &ds, const void *h, int M, void *x, hipStream_t st) {
