@@ -59,15 +59,16 @@ __device__ __forceinline__ double wave_max(double v) {
 }
 
 // x = row / sqrt(mean of squares) in fp32 for one row held by a workgroup of kRmsThreads threads: thread i holds the
-// elements (c * kRmsThreads + i) * 4 .. + 3 of chunk c = 0 .. 7 in v[c][0..3] (zeros past the row end).  Squares are
+// elements (c * kRmsThreads + i) * 4 .. + 3 of chunk c = 0 .. kRmsChunks-1 in v[c][0..3] (zeros past the row end;
+// the hidden size is at most 8192).  Squares are
 // added chunk by chunk and element by element per thread, the per-thread sums pairwise through LDS (a fixed tree):
 // the result depends on the values alone.  Used by rms_scale_kernel and by the combine that also writes the next
 // layer's input, which therefore agree bit for bit.  part: kRmsThreads floats of LDS.  Synchronises.
-constexpr int kRmsThreads = 256;
-__device__ inline float rms_scale_of_row(const float (&v)[8][4], int d, float *part) {
+constexpr int kRmsThreads = 1024, kRmsChunks = 2;
+__device__ inline float rms_scale_of_row(const float (&v)[kRmsChunks][4], int d, float *part) {
   float ss = 0.f;
 #pragma unroll
-  for (int c = 0; c < 8; ++c)
+  for (int c = 0; c < kRmsChunks; ++c)
 #pragma unroll
     for (int i = 0; i < 4; ++i) ss = fmaf(v[c][i], v[c][i], ss);
   part[threadIdx.x] = ss;

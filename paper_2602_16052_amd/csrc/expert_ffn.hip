@@ -784,7 +784,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
 // The combine of a layer inside a stack that scales its layer inputs: one workgroup per token writes the row of the
 // new hidden state and, from the STORED (rounded) values, the next layer's input x = row / rms(row) - with the
 // element-to-thread mapping and summation order of rms_scale_row, so that the result equals, bit for bit, what
-// rms_scale_kernel makes of the stored row.  d <= 8192: a thread holds up to 32 outputs.
+// rms_scale_kernel makes of the stored row.  d <= 8192: a thread holds up to 8 outputs.
 template <typename T>
 __global__ __launch_bounds__(kRmsThreads) void combine_scale_kernel(const float *__restrict__ y,
                                                                     const int32_t *__restrict__ tok_ids,
@@ -794,9 +794,9 @@ __global__ __launch_bounds__(kRmsThreads) void combine_scale_kernel(const float 
                                                                     T *__restrict__ out, T *__restrict__ x_next) {
   __shared__ float part[kRmsThreads];
   const int t = blockIdx.x, tid = threadIdx.x;
-  float v[8][4];
+  float v[kRmsChunks][4];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
+  for (int c = 0; c < kRmsChunks; ++c) {
     const int j = (c * kRmsThreads + tid) * 4;
     if (j < d) {
       const f32x4 acc = combine_four<T>(y, tok_ids, tok_w, residual, t, j, k, d, splits, split_stride);
@@ -812,7 +812,7 @@ __global__ __launch_bounds__(kRmsThreads) void combine_scale_kernel(const float 
   }
   const float scale = rms_scale_of_row(v, d, part);
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
+  for (int c = 0; c < kRmsChunks; ++c) {
     const int j = (c * kRmsThreads + tid) * 4;
     if (j < d)
 #pragma unroll

@@ -11,16 +11,16 @@ template <typename T>
 __global__ __launch_bounds__(kRmsThreads) void rms_scale_kernel(const T *__restrict__ h, int d, T *x) {
   __shared__ float part[kRmsThreads];
   const int t = blockIdx.x, tid = threadIdx.x;
-  float v[8][4];
+  float v[kRmsChunks][4];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
+  for (int c = 0; c < kRmsChunks; ++c) {
     const int j = (c * kRmsThreads + tid) * 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) v[c][i] = j < d ? Elem<T>::load(h + (size_t)t * d + j + i) : 0.f;
   }
   const float scale = rms_scale_of_row(v, d, part);
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
+  for (int c = 0; c < kRmsChunks; ++c) {
     const int j = (c * kRmsThreads + tid) * 4;
     if (j < d)
 #pragma unroll
