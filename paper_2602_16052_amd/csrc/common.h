@@ -258,7 +258,7 @@ bool fused_prologue_ok(const moespec_desc &ds, int M);
 bool mfma_route_ok(const moespec_desc &ds, int M);
 hipError_t launch_mfma_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *partial,
                              double *probs, int32_t *zero_words, int n_zero, hipStream_t st);
-int logit_slices(const moespec_desc &ds, int M);
+int logit_slices(const moespec_desc &ds, int M, bool whole_table);
 hipError_t launch_fused_prologue(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, int B,
                                  int policy, const int32_t *ext_shortlist, double *partial, double *probs_ws,
                                  double *probs_out,

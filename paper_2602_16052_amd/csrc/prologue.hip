@@ -574,10 +574,11 @@ bool fused_prologue_ok(const moespec_desc &ds, int M) {
 }
 
 // Slices of the hidden dimension (1, 2, 4 or 8): more slices spread the matrix work over more compute units
-// (a wave issues one fp64 matrix instruction per 64 cycles), but every workgroup of the second kernel re-reads
-// one partial table per slice.  Picks the count with the smallest estimated sum of the two (rates measured on
-// MI355X: 2.4 GHz, about 150 GB/s from L2 into one compute unit).
-int logit_slices(const moespec_desc &ds, int M) {
+// (a wave issues one fp64 matrix instruction per 64 cycles), but the consumer re-reads one partial table per
+// slice: every workgroup of the fused kernel the whole table (whole_table), the row-wise gate kernel one row.
+// Picks the count with the smallest estimated sum of the two (rates measured on MI355X: 2.4 GHz, about 150 GB/s
+// from L2 into one compute unit).
+int logit_slices(const moespec_desc &ds, int M, bool whole_table) {
   const double tiles = ((M + 15) / 16) * ((ds.n_experts + 15) / 16), n_blocks = ds.d / 32;
   int best = 1;
   double best_us = 1e30;
@@ -585,7 +586,7 @@ int logit_slices(const moespec_desc &ds, int M) {
     if (q > 1 && n_blocks < 2.0 * q * kLogitWaves) break;  // at least two 32-element blocks per wave
     const double waves_per_simd = tiles * q * kLogitWaves / 1024.0;  // 256 compute units x 4 SIMDs
     const double mfma_us = (n_blocks / (q * kLogitWaves)) * 8 * 64 / 2400.0 * (waves_per_simd > 1 ? waves_per_simd : 1);
-    const double read_us = q * 8.0 * M * ds.n_experts / 150e3;
+    const double read_us = q * 8.0 * (whole_table ? M : 1) * ds.n_experts / 150e3;
     if (mfma_us + read_us < best_us) {
       best_us = mfma_us + read_us;
       best = q;
@@ -601,7 +602,7 @@ bool mfma_route_ok(const moespec_desc &ds, int M) {
 }
 hipError_t launch_mfma_route(const moespec_desc &ds, const moespec_weights &wt, const void *h, int M, double *partial,
                              double *probs, int32_t *zero_words, int n_zero, hipStream_t st) {
-  const int N = ds.n_experts, q = logit_slices(ds, M), sig = ds.gate == MOESPEC_GATE_SIGMOID ? 1 : 0;
+  const int N = ds.n_experts, q = logit_slices(ds, M, false), sig = ds.gate == MOESPEC_GATE_SIGMOID ? 1 : 0;
   dim3 grid(((M + 15) / 16) * ((N + 15) / 16), q);
   logits_mfma_kernel<<<grid, kLogitWaves * kWave, 0, st>>>(static_cast<const uint16_t *>(h),
                                                           static_cast<const uint16_t *>(wt.w_router), M, N, ds.d, q,
@@ -624,7 +625,10 @@ hipError_t launch_fused_prologue(const moespec_desc &ds, const moespec_weights &
                                  float *tok_w, int32_t *list_count, int32_t *lists, int list_stride,
                                  int32_t *seg_off, int32_t *perm, int32_t *n_loaded, hipStream_t st) {
   const int N = ds.n_experts, k = ds.top_k;
-  const int q = logit_slices(ds, M);
+  // Large tables: the routing probabilities are finished row by row in a launch of their own and the last kernel
+  // only loads them; small tables: every workgroup of the last kernel rebuilds the table itself.
+  const bool split = (long long)M * N > kSplitSoftmaxAbove;
+  const int q = logit_slices(ds, M, !split);
   dim3 grid(((M + 15) / 16) * ((N + 15) / 16), q);
   logits_mfma_kernel<<<grid, kLogitWaves * kWave, 0, st>>>(static_cast<const uint16_t *>(h),
                                                           static_cast<const uint16_t *>(wt.w_router), M, N, ds.d, q,
@@ -633,9 +637,6 @@ hipError_t launch_fused_prologue(const moespec_desc &ds, const moespec_weights &
   if (e != hipSuccess) return e;
   const size_t smem = prologue_lds(M, N, k, B).total;
   const int sig = ds.gate == MOESPEC_GATE_SIGMOID ? 1 : 0;
-  // Large tables: the routing probabilities are finished row by row in a launch of their own and the last kernel
-  // only loads them; small tables: every workgroup of the last kernel rebuilds the table itself.
-  const bool split = (long long)M * N > kSplitSoftmaxAbove;
   const double *table = partial;
   const float *table_bias = wt.b_router;
   int slices = q;
