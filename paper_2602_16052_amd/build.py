@@ -39,5 +39,22 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def build_host_sanitizer_library(out_dir: str) -> str:
+    """The library with AddressSanitizer and UndefinedBehaviorSanitizer instrumentation in its HOST code only
+    (GPU sanitizers are not used); the device code is compiled unoptimised to keep the build short.  For the
+    host-side checks in tests/; never loaded by the product path.  Returns the path of the library."""
+    out = os.path.join(out_dir, "libmoespec_hostsan.so")
+    flags = [f for f in HIPCC_FLAGS if f != "-O3"]
+    cmd = [hipcc_path(), *flags, "-Xarch_device", "-O0", "-Xarch_host", "-O1",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, *[os.path.join(CSRC, s) for s in SOURCES], "-o", out]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + "\n".join(l for l in res.stdout.splitlines()
+                                                          if "packed-fp32-ops" not in l))
+    return out
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
