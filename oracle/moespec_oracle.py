@@ -112,11 +112,17 @@ def top_k(g_row, k: int) -> List[int]:
 
 
 def mixing_weights(g_row, ids: Sequence[int], renorm: bool) -> List[float]:
-    """g-bar over the selected set: raw g_i, or g_i / sum_{j in ids} g_j."""
+    """g-bar over the selected set: raw g_i, or g_i / sum_{j in ids} g_j.
+
+    If every selected expert has probability exactly 0 in fp64 (router logits more than 745 apart: substitution
+    inside a shortlist that holds none of the token's own experts) the renormalised weights are 0/0; the paper
+    does not cover the case and the reading is IEEE arithmetic: NaN for every slot of that token."""
     if renorm:
         denom = 0.0
         for j in ids:
             denom += float(g_row[j])
+        if denom == 0.0:
+            return [float("nan")] * len(ids)
         return [float(g_row[i]) / denom for i in ids]
     return [float(g_row[i]) for i in ids]
 

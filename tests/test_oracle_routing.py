@@ -394,3 +394,27 @@ def test_sigmoid_gate_changes_the_aggregate_ranking_but_not_the_full_budget_laye
     # one hot logit far above the rest: softmax gives it all the mass, sigmoid leaves the others near 1/2
     z = np.array([[20.0, 0.1, 0.0, -0.1]])
     assert O.routing_probs(z, O.SOFTMAX)[0, 1] < 1e-8 and abs(O.routing_probs(z, O.SIGMOID)[0, 1] - 0.525) < 1e-3
+
+
+# ------------------------------------------------------------------------- softmax underflow, zero mass
+def test_logits_hundreds_apart_underflow_to_exact_zeros_and_zero_mass_renormalises_to_nan():
+    """Max-subtracted fp64 softmax: experts more than 745 below the row maximum get probability exactly 0, ties
+    among them go to the lowest id, and a substitution set that holds only such experts has renormalised
+    weights 0/0 = NaN (raw weights are 0)."""
+    logits = np.array([[0.0, -10.0, -800.0, -900.0, -1000.0],
+                       [-2000.0, 3.0, 1.0, -3000.0, 2.0]])
+    g = O.routing_probs(logits, O.SOFTMAX)
+    assert g[0, 2] == g[0, 3] == g[0, 4] == 0.0 and g[0, 0] > 0.9999 and 0 < g[0, 1] < 1e-4
+    assert g[1, 0] == g[1, 3] == 0.0
+    np.testing.assert_allclose(g.sum(axis=1), 1.0, rtol=1e-15)
+    assert O.top_k(g[0], 4) == [0, 1, 2, 3]                     # zeros tie: lowest ids first
+    S = [2, 3, 4]                                              # a shortlist without token 0's own experts
+    ids, w = O.restrict_substitution(g, S, 2, True)
+    assert list(ids[0]) == [2, 3] and np.all(np.isnan(w[0]))    # zero mass: 0/0
+    assert list(ids[1]) == [4, 2] and np.all(np.isfinite(w[1]))     # descending probability
+    np.testing.assert_allclose(w[1], g[1][[4, 2]] / (g[1, 2] + g[1, 4]), rtol=1e-15)
+    ids_raw, w_raw = O.restrict_substitution(g, S, 2, False)
+    assert list(ids_raw[0]) == [2, 3] and np.all(w_raw[0] == 0.0)
+    # truncation never meets zero mass: its weights are those of the natural top-k, which holds the row maximum
+    nat = O.top_k(g[0], 2)
+    assert np.all(np.isfinite(O.mixing_weights(g[0], nat, True)))
