@@ -29,6 +29,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gateup_olmoe_m63_B32_hbm_traffic.md")
+TRACE_PROFILE = os.path.join(ROOT, "profiles", "bench_olmoe_m63_B32_kernel_trace.md")
 TOL_BF16 = 2e-2
 
 
@@ -75,6 +76,17 @@ def stored_traffic():
     if sha != source_hash():
         return None, f"counter summary under profiles/ was measured on another build ({sha})"
     return val, "FETCH_SIZE + WRITE_SIZE of profiles/" + os.path.basename(TRAFFIC_PROFILE)
+
+
+def stored_kernel_trace():
+    """Average gate/up kernel duration (ms) of the tracked rocprofv3 kernel-trace summary, if measured on this build."""
+    try:
+        text = open(TRACE_PROFILE).read()
+        sha = re.search(r"csrc_sha256_16:\s*([0-9a-f]{16})", text).group(1)
+        us = float(re.search(r"gateup_kernel_trace_avg_us:\s*([0-9.]+)", text).group(1))
+    except (OSError, AttributeError):
+        return None
+    return us * 1e-3 if sha == source_hash() else None
 
 
 def timed_steps(torch, calls, steps, warmup):
@@ -282,8 +294,19 @@ def main():
         stream_gbps = 3 * big.numel() / (ev.elapsed_ms(0, 1) * 1e-3) / 1e9
         del big
 
+    # what an event interval carries besides the kernel: two records with nothing between them, on an idle stream
+    ev = mb.HipEvents(2)
+    empty = []
+    for _ in range(50):
+        ev.record(0)
+        ev.record(1)
+        torch.cuda.synchronize()
+        empty.append(ev.elapsed_ms(0, 1))
+    event_overhead_ms = sorted(empty)[len(empty) // 2]
+
     default_workload = (args.config, args.budget, args.policy, args.sets) == ("olmoe_m63", 32, "substitution", 6)
     traffic, traffic_note = stored_traffic() if default_workload else (None, "measured for the default workload only")
+    trace_ms = stored_kernel_trace() if default_workload else None
     result = {
         "metric": "verified tree-tokens/s per MoE layer",
         "value": round(tokens_per_s, 1),
@@ -308,7 +331,11 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(gateup_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "traffic_source": traffic_note, "build": source_hash(),
                      "algorithmic_bytes_per_launch": gateup_bytes,
-                     "avg_launch_ms": round(stage_ms["gate_up"], 5), "down_pass_GBps": round(down_gbps, 1),
+                     "avg_launch_ms": round(stage_ms["gate_up"], 5),
+                     "empty_event_interval_ms": round(event_overhead_ms, 5),
+                     "kernel_trace_avg_launch_ms": round(trace_ms, 5) if trace_ms else None,
+                     "kernel_trace_frac": round(gateup_bytes / trace_ms / 1e6 / HBM_PEAK_GBPS, 4) if trace_ms else None,
+                     "down_pass_GBps": round(down_gbps, 1),
                      "stream_read_GBps": round(stream_gbps, 1) if stream_gbps else None},
         "stage_ms": {k_: round(v, 5) for k_, v in stage_ms.items()},
         "ms_per_step_traced": round(ms_traced, 5),
