@@ -96,3 +96,22 @@ def test_stored_stack_scales_show_why_the_stack_scales_its_layer_inputs(golden_d
     assert len(pre) == 8 and all(r["next_state_finite_in_bf16"] for r in pre)
     outs = [r["moe_output_max_abs"] for r in pre]
     assert max(outs) / min(outs) < 1.5, outs
+
+
+def test_tracked_counter_summaries_were_measured_on_the_current_kernel_sources():
+    """bench.py reports `roofline.traffic` and the kernel-trace duration only from summaries whose build id equals
+    the hash of the kernel sources; a summary left behind by a kernel change would silently drop them."""
+    import glob
+    import os
+    import re
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    current = bench.source_hash()
+    files = sorted(glob.glob(os.path.join(root, "profiles", "*.md")))
+    assert files
+    for f in files:
+        ids = re.findall(r"csrc_sha256_16:\s*([0-9a-f]{16})", open(f).read())
+        assert ids and all(i == current for i in ids), (os.path.basename(f), ids, current)
+    assert bench.stored_traffic()[0] > 0 and bench.stored_kernel_trace() > 0
